@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the AdaFuse hot path on one MI355X.
+
+A step = one token: the pre-gating router on that token's hidden state followed
+by one fused switch (SWAP: previous token's experts out, this token's in) over
+every adapted matrix of the model, both enqueued on one stream with no host
+round trip in between.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: the metric (switch latency per token, lower is better),
+the HBM roofline of the dominant kernel measured with HIP events on the launch
+stream, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="llama2_7b_all")
+    ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--mode", default="swap", choices=["swap", "unmerge"],
+                    help="unmerge times the plain W_base->W_work copy over the same tile table")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=1, help="layers of the model the oracle is timed on")
+    return ap.parse_args()
+
+
+def read_traffic(workload, kernel_name):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"switch_{kernel_name}_{workload}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(wl, mats, hidden, router, idx_t, gates_t, n_layers):
+    """Time the oracle (as it stands) on the first n_layers of the model, one switch."""
+    import numpy as np
+    import adafuse_workloads as wlmod
+    import oracle
+    per_layer = len(wl.mats)
+    sample = mats[: n_layers * per_layer]
+    host = [(wlmod.bits(wb), wlmod.bits(a), wlmod.bits(b)) for wb, _, a, b in sample]
+    hb, rb = wlmod.bits(hidden[:1]), wlmod.bits(router)
+    idx = np.asarray(idx_t, np.int32)
+    gates = np.asarray(gates_t, np.float32)
+    oracle.lib()
+    t0 = time.perf_counter()
+    oracle.pregate(hb, rb, wl.k)
+    for w, a, b in host:
+        oracle.merge(w, a, b, idx, gates, wl.scale)
+    dt = time.perf_counter() - t0
+    elems = sum(w.size for w, _, _ in host)
+    full = dt * wl.elements / elems
+    return {"value": full * 1e6, "unit": "us/token", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"one switch of the first {n_layers} of {wl.layers} layers ({len(host)} matrices, "
+                      f"{elems} elements) in {dt:.2f} s, scaled by element count to the full model"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import adafuse_workloads as wlmod
+    import paper_2603_11873_amd as af
+
+    af.load_library()          # fails loudly if the HIP library is not built
+    wl = wlmod.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    mats = []
+    for layer in range(wl.layers):
+        for mi in range(len(wl.mats)):
+            wb = wlmod.gen_w(wl, layer, mi, "cuda")
+            mats.append((wb, torch.empty_like(wb), wlmod.gen_a_bank(wl, layer, mi, "cuda"),
+                         wlmod.gen_b_bank(wl, layer, mi, "cuda")))
+    hidden = wlmod.gen_hidden(wl, "cuda")
+    router = wlmod.gen_router(wl, "cuda")
+    ctx = af.Context(mats, wl.k)
+    ctx.set_kernel({"auto": af.KERNEL_AUTO, "valu": af.KERNEL_VALU, "mfma": af.KERNEL_MFMA}[args.kernel])
+    info = ctx.info()
+    kernel_name = {af.KERNEL_VALU: "valu", af.KERNEL_MFMA: "mfma"}[info.kernel]
+
+    T = wl.T
+    idx = torch.empty((T, wl.k), dtype=torch.int32, device=dev)
+    gates = torch.empty((T, wl.k), dtype=torch.float32, device=dev)
+    stream = torch.cuda.Stream(device=dev)
+    mode = af.SWAP if args.mode == "swap" else af.UNMERGE
+
+    def step(t, ev=None):
+        """Router for token t, then the fused switch from token t-1's decision to t's."""
+        cur, prv = t % T, (t - 1) % T
+        af.pregate(hidden[cur:cur + 1], router, wl.k, out=(idx[cur:cur + 1], gates[cur:cur + 1], None), stream=stream)
+        if ev is not None:
+            ev[0].record(stream)
+        ctx.fused_switch(idx[prv], gates[prv], idx[cur], gates[cur], wl.k, wl.scale, mode, stream=stream)
+        if ev is not None:
+            ev[1].record(stream)
+
+    with torch.cuda.stream(stream):
+        # the decision "before the first token": token T-1's
+        af.pregate(hidden, router, wl.k, out=(idx, gates, None), stream=stream)
+        for t in range(args.warmup):
+            step(t)
+        events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                  for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(args.steps):
+            step(args.warmup + t, events[t])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    kernel_ms = [a.elapsed_time(b) for a, b in events]           # the switch launch alone
+    avg_kernel_s = sum(kernel_ms) / len(kernel_ms) * 1e-3
+    alg_bytes = wl.algorithmic_bytes if mode == af.SWAP else 4 * wl.elements
+    achieved = alg_bytes / avg_kernel_s / 1e9
+    srt = sorted(kernel_ms)
+
+    out = {
+        "metric": "fused-switch latency per token, all layers (us) + achieved HBM GB/s vs peak",
+        "value": ms_per_step * 1e3,
+        "unit": "us/token",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "layers": wl.layers, "matrices": wl.n_mats, "elements": wl.elements,
+                   "E": wl.E, "r": wl.r, "k": wl.k, "tokens": T, "scale": wl.scale, "mode": args.mode,
+                   "kernel": kernel_name, "tile": [info.tile_rows, info.tile_cols], "workgroups": info.n_tiles,
+                   "step": "pregate(1 token) + fused_switch(all matrices), one stream"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": read_traffic(wl.name, kernel_name) if mode == af.SWAP else None,
+                     "kernel": f"switch_{kernel_name}_kernel" if mode == af.SWAP else "switch_copy_kernel",
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "kernel_us": {"mean": avg_kernel_s * 1e6, "median": srt[len(srt) // 2] * 1e3,
+                                   "p95": srt[int(0.95 * (len(srt) - 1))] * 1e3, "min": srt[0] * 1e3}},
+    }
+    if not args.no_cpu_baseline:
+        t = (args.warmup + args.steps - 1) % T
+        out["cpu_baseline"] = cpu_baseline(wl, mats, hidden, router, idx[t].cpu().numpy(),
+                                           gates[t].cpu().numpy(), min(args.cpu_layers, wl.layers))
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,168 @@
+/*
+ * libadafuse -- the fused adapter switch of AdaFuse on one MI355X (gfx950).
+ *
+ * Two operations, each one kernel launch on a caller-supplied HIP stream:
+ *
+ *   adafuse_pregate       token-level pre-gating router G^1(x^1): one linear map,
+ *                         top-k and softmax per token, decided once and reused by
+ *                         every adapted layer (paper: Eq.1 for the form of G,
+ *                         Eq.2 and section "Model Structure" for its single use).
+ *   adafuse_fused_switch  for EVERY adapted matrix of the model at once,
+ *                         W' = W + s * sum_{j<k} g_j * B_{e_j} A_{e_j}
+ *                         (Eq.4-6, merge), with the previous token's merge removed
+ *                         in the same pass (Eq.7-8, fused switch), executed as one
+ *                         batched launch over a table of matrix pointers and
+ *                         shapes (Eq.9 and section "SGMM Kernel").
+ *
+ * Layout conventions (y = W x, as torch.nn.Linear stores it):
+ *   W        bf16 [out][ldw]   row-major, ldw >= in (elements)
+ *   A bank   bf16 [E][r][in]   expert e's LoRA_DOWN
+ *   B bank   bf16 [E][out][r]  expert e's LoRA_UP
+ *   dW = sum_j (s*g_j) * B_{e_j} A_{e_j}     (the paper's "DOWN x UP")
+ *
+ * Every pointer marked DEVICE must be device memory reachable from the current
+ * HIP device; HOST pointers are ordinary host memory.  Nothing here takes or
+ * returns a framework type.  All functions return an adafuse_status; none
+ * throws, aborts or prints.  Argument checks that need no GPU run before any
+ * HIP call, so invalid arguments are reported on a machine without a GPU too.
+ */
+#ifndef ADAFUSE_H
+#define ADAFUSE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct adafuse_ctx adafuse_ctx; /* opaque */
+
+typedef enum {
+    ADAFUSE_OK = 0,
+    ADAFUSE_ERR_NULL = 1,  /* a required pointer is NULL */
+    ADAFUSE_ERR_ARG = 2,   /* a scalar argument is out of range */
+    ADAFUSE_ERR_SHAPE = 3, /* a matrix shape is unsupported */
+    ADAFUSE_ERR_ALIGN = 4, /* a pointer or leading dimension is misaligned */
+    ADAFUSE_ERR_HIP = 5    /* a HIP runtime call failed */
+} adafuse_status;
+
+typedef enum {
+    ADAFUSE_MERGE = 0,   /* W_work <- rn(W_base + dW(next)); prev ignored */
+    ADAFUSE_UNMERGE = 1, /* W_work <- W_base, bit-exact; next ignored */
+    ADAFUSE_SWAP = 2     /* remove prev, add next, in one pass (see adafuse_fused_switch) */
+} adafuse_mode;
+
+typedef enum {
+    ADAFUSE_GATE_SOFTMAX_OVER_TOPK = 0, /* Eq.1: softmax over the k kept logits; gates sum to 1 */
+    ADAFUSE_GATE_TOPK_OF_SOFTMAX = 1    /* "Router Architecture": softmax over all E, keep k */
+} adafuse_gate_norm;
+
+typedef enum {
+    ADAFUSE_KERNEL_AUTO = 0, /* library's choice for the context's (r, k_max) */
+    ADAFUSE_KERNEL_VALU = 1, /* rank-(k r) update on the vector ALU, fp32 */
+    ADAFUSE_KERNEL_MFMA = 2  /* per-expert B_e A_e on the matrix cores (bf16 in, fp32 out) */
+} adafuse_kernel;
+
+/*
+ * One adapted linear matrix (one entry of the pointer/shape arrays the SGMM
+ * kernel takes, section "SGMM Kernel").  All pointers are DEVICE pointers, 16-byte
+ * aligned, owned by the caller and must stay valid while the context lives.
+ * w_base is never written.  w_work is the matrix the model's forward pass reads.
+ * w_work must not overlap w_base or any bank.
+ */
+typedef struct {
+    const void *w_base; /* bf16 [out][ldw] */
+    void *w_work;       /* bf16 [out][ldw] */
+    const void *a_bank; /* bf16 [E][r][in] */
+    const void *b_bank; /* bf16 [E][out][r] */
+    int32_t out;        /* rows, >= 1 */
+    int32_t in;         /* columns, >= 8 and a multiple of 8 */
+    int32_t ldw;        /* leading dimension of both W buffers, >= in, multiple of 8 */
+    int32_t reserved;   /* must be 0 */
+} adafuse_matrix_desc;
+
+typedef struct {
+    int32_t n_mats;
+    int32_t E, r, k_max;
+    int32_t kernel;          /* adafuse_kernel in effect (never AUTO) */
+    int32_t tile_rows;       /* rows x cols of W one workgroup handles */
+    int32_t tile_cols;
+    int32_t reserved;
+    int64_t n_tiles;         /* workgroups per switch launch */
+    int64_t elements;        /* sum of out*in over all matrices */
+} adafuse_info;
+
+/*
+ * Build a context for a fixed set of adapted matrices: copies `mats` (HOST array
+ * of n_mats descriptors; may be freed afterwards), builds the matrix and tile
+ * tables the switch kernel walks and uploads them to the current device.  This
+ * is the only call that allocates device memory or synchronises; the tables are
+ * a few bytes per tile.  E = experts per bank, r = LoRA rank (4, 8, 16, 32 or
+ * 64), k_max = largest k any later call will pass (1 <= k_max <= min(E, 8)).
+ * Errors: NULL mats/ctx or NULL pointer inside a descriptor -> ERR_NULL;
+ * n_mats < 1, bad E/r/k_max, reserved != 0, w_work == w_base -> ERR_ARG;
+ * out < 1, in < 8, in % 8, ldw < in, ldw % 8 -> ERR_SHAPE; pointer not 16-byte
+ * aligned -> ERR_ALIGN; HIP failure -> ERR_HIP (no context is returned).
+ */
+adafuse_status adafuse_create(const adafuse_matrix_desc *mats, int32_t n_mats,
+                              int32_t E, int32_t r, int32_t k_max, adafuse_ctx **ctx);
+
+/* Free the context's tables.  NULL is accepted.  Caller buffers are untouched. */
+adafuse_status adafuse_destroy(adafuse_ctx *ctx);
+
+/* Choose the switch kernel (adafuse_kernel).  Rebuilds the tile table if the
+ * tile shape changes (allocates and synchronises like adafuse_create). */
+adafuse_status adafuse_set_kernel(adafuse_ctx *ctx, int32_t kernel);
+
+/* Fill *info (HOST) with the context's geometry. */
+adafuse_status adafuse_get_info(const adafuse_ctx *ctx, adafuse_info *info);
+
+/*
+ * Pre-gating router for T tokens (Eq.1's G applied to x^1, Eq.2):
+ *   logits[t][e] = sum_i hidden[t][i] * w_router[e][i]      (fp32 result)
+ *   idx[t][0..k)  = the k largest logits of token t, ordered by (logit
+ *                   descending, expert index ascending); ties take the lower index
+ *   gates[t][j]   = softmax per gate_norm, fp32
+ * hidden   DEVICE bf16 [T][d], w_router DEVICE bf16 [E][d], both 16-byte aligned,
+ *          d a multiple of 8; 1 <= k <= E <= 64; T >= 0 (T == 0 is a no-op).
+ * idx      DEVICE int32 [T][k], gates DEVICE fp32 [T][k], logits DEVICE fp32
+ *          [T][E] or NULL.  Outputs are written by the kernel on `hip_stream`
+ *          (a hipStream_t, NULL = default stream); the call does not wait.
+ * Selection and gates are taken from the fp32 logits the call returns.
+ */
+adafuse_status adafuse_pregate(const void *hidden, const void *w_router,
+                               int32_t T, int32_t d, int32_t E, int32_t k, int32_t gate_norm,
+                               int32_t *idx, float *gates, float *logits, void *hip_stream);
+
+/*
+ * Fused adapter switch over every matrix of the context, one launch (Eq.8-9).
+ *   idx_next/gates_next  DEVICE int32[k] / fp32[k]: the token's experts and gates
+ *   idx_prev/gates_prev  DEVICE, same shapes: what the previous call merged
+ *   k      1 <= k <= k_max;   scale = LoRA scaling s
+ * MERGE   W_work <- rn_bf16(W_base + s * sum_j gates_next[j] B_{idx_next[j]} A_{idx_next[j]}),
+ *         fp32 accumulation, one rounding.  prev may be NULL.
+ * UNMERGE W_work <- W_base bit-exact.  prev and next may be NULL.
+ * SWAP    the fused switch: the result is that of MERGE(next).  Because W_work is
+ *         rebuilt from the immutable W_base, the previous token's update is
+ *         removed exactly (no bf16 drift) and Eq.8's signed concatenation needs
+ *         no arithmetic.  prev, if not NULL, is only compared with next on the
+ *         device: when both are bit-identical W_work already holds the result
+ *         and the kernel returns without touching it.
+ * Each W element is read once and written once (2 + 2 bytes); the selected A/B
+ * slices are staged in LDS.  Expert indices outside [0,E) in device memory are
+ * clamped into range, not detected.  The call enqueues on `hip_stream` and
+ * returns; no host synchronisation.
+ * Errors: NULL ctx or a NULL pointer the mode needs -> ERR_NULL; bad k or mode ->
+ * ERR_ARG; launch failure -> ERR_HIP.
+ */
+adafuse_status adafuse_fused_switch(adafuse_ctx *ctx,
+                                    const int32_t *idx_prev, const float *gates_prev,
+                                    const int32_t *idx_next, const float *gates_next,
+                                    int32_t k, float scale, int32_t mode, void *hip_stream);
+
+const char *adafuse_status_string(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADAFUSE_H */

@@ -1,0 +1,164 @@
+"""ctypes binding with the same names as the C ABI (include/adafuse.h)."""
+import ctypes as C
+import os
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(PKG, "libadafuse.so")
+_lib = None
+
+MERGE, UNMERGE, SWAP = 0, 1, 2
+GATE_SOFTMAX_OVER_TOPK, GATE_TOPK_OF_SOFTMAX = 0, 1
+KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
+
+EXPORTS = ["adafuse_create", "adafuse_destroy", "adafuse_set_kernel", "adafuse_get_info",
+           "adafuse_pregate", "adafuse_fused_switch", "adafuse_status_string"]
+
+
+class AdafuseError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = int(status)
+        msg = load_library().adafuse_status_string(self.status).decode()
+        super().__init__(f"{what}: {msg} (status {self.status})")
+
+
+class MatrixDesc(C.Structure):
+    """adafuse_matrix_desc"""
+    _fields_ = [("w_base", C.c_void_p), ("w_work", C.c_void_p), ("a_bank", C.c_void_p), ("b_bank", C.c_void_p),
+                ("out", C.c_int32), ("in_", C.c_int32), ("ldw", C.c_int32), ("reserved", C.c_int32)]
+
+
+class Info(C.Structure):
+    """adafuse_info"""
+    _fields_ = [("n_mats", C.c_int32), ("E", C.c_int32), ("r", C.c_int32), ("k_max", C.c_int32),
+                ("kernel", C.c_int32), ("tile_rows", C.c_int32), ("tile_cols", C.c_int32), ("reserved", C.c_int32),
+                ("n_tiles", C.c_int64), ("elements", C.c_int64)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libadafuse.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2603_11873_amd.build` "
+                          "(or __graft_entry__.build()); there is no fallback path")
+    L = C.CDLL(_LIB_PATH)
+    vp, i32, f32 = C.c_void_p, C.c_int32, C.c_float
+    L.adafuse_create.restype = i32
+    L.adafuse_create.argtypes = [C.POINTER(MatrixDesc), i32, i32, i32, i32, C.POINTER(vp)]
+    L.adafuse_destroy.restype = i32
+    L.adafuse_destroy.argtypes = [vp]
+    L.adafuse_set_kernel.restype = i32
+    L.adafuse_set_kernel.argtypes = [vp, i32]
+    L.adafuse_get_info.restype = i32
+    L.adafuse_get_info.argtypes = [vp, C.POINTER(Info)]
+    L.adafuse_pregate.restype = i32
+    L.adafuse_pregate.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
+    L.adafuse_fused_switch.restype = i32
+    L.adafuse_fused_switch.argtypes = [vp, vp, vp, vp, vp, i32, f32, i32, vp]
+    L.adafuse_status_string.restype = C.c_char_p
+    L.adafuse_status_string.argtypes = [i32]
+    _lib = L
+    return L
+
+
+def _ptr(t):
+    """Device (or host) address of a torch tensor, or NULL."""
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream_handle(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def pregate(hidden, w_router, k, gate_norm=GATE_SOFTMAX_OVER_TOPK, want_logits=True, stream=None, out=None):
+    """adafuse_pregate on torch tensors: hidden bf16 [T][d], w_router bf16 [E][d] (device).
+
+    Returns (idx int32 [T][k], gates fp32 [T][k], logits fp32 [T][E] or None), device tensors
+    written asynchronously on `stream` (default: torch's current stream).
+    """
+    import torch
+    T, d = hidden.shape
+    E = w_router.shape[0]
+    assert hidden.dtype == torch.bfloat16 and w_router.dtype == torch.bfloat16
+    assert hidden.is_contiguous() and w_router.is_contiguous() and w_router.shape[1] == d
+    if out is None:
+        idx = torch.empty((T, k), dtype=torch.int32, device=hidden.device)
+        gates = torch.empty((T, k), dtype=torch.float32, device=hidden.device)
+        logits = torch.empty((T, E), dtype=torch.float32, device=hidden.device) if want_logits else None
+    else:
+        idx, gates, logits = out
+    st = load_library().adafuse_pregate(_ptr(hidden), _ptr(w_router), T, d, E, k, gate_norm,
+                                        _ptr(idx), _ptr(gates), _ptr(logits), _stream_handle(stream))
+    if st != 0:
+        raise AdafuseError(st, "adafuse_pregate")
+    return idx, gates, logits
+
+
+class Context:
+    """adafuse_ctx: a fixed set of adapted matrices.
+
+    mats: list of (w_base, w_work, a_bank, b_bank) torch bf16 device tensors with
+    shapes [out][in], [out][in], [E][r][in], [E][out][r].  The context keeps
+    references so the memory outlives it.
+    """
+
+    def __init__(self, mats, k_max):
+        import torch
+        self._keep = list(mats)
+        n = len(self._keep)
+        arr = (MatrixDesc * max(n, 1))()
+        E = r = None
+        for i, (wb, ww, a, b) in enumerate(self._keep):
+            for t in (wb, ww, a, b):
+                assert t.dtype == torch.bfloat16 and t.is_cuda
+            assert a.is_contiguous() and b.is_contiguous()
+            out, in_ = wb.shape
+            assert ww.shape == wb.shape and wb.stride(1) == 1 and ww.stride(1) == 1 and wb.stride(0) == ww.stride(0)
+            assert a.shape[0] == b.shape[0] and a.shape[2] == in_ and b.shape[1] == out and a.shape[1] == b.shape[2]
+            if E is None:
+                E, r = a.shape[0], a.shape[1]
+            assert (E, r) == (a.shape[0], a.shape[1])
+            arr[i] = MatrixDesc(wb.data_ptr(), ww.data_ptr(), a.data_ptr(), b.data_ptr(), out, in_, wb.stride(0), 0)
+        self.E, self.r, self.k_max = E or 0, r or 0, k_max
+        self._h = C.c_void_p()
+        st = load_library().adafuse_create(arr, n, self.E, self.r, k_max, C.byref(self._h))
+        if st != 0:
+            raise AdafuseError(st, "adafuse_create")
+
+    def set_kernel(self, kernel):
+        st = load_library().adafuse_set_kernel(self._h, kernel)
+        if st != 0:
+            raise AdafuseError(st, "adafuse_set_kernel")
+
+    def info(self) -> Info:
+        info = Info()
+        st = load_library().adafuse_get_info(self._h, C.byref(info))
+        if st != 0:
+            raise AdafuseError(st, "adafuse_get_info")
+        return info
+
+    def fused_switch(self, idx_prev, gates_prev, idx_next, gates_next, k, scale, mode, stream=None):
+        """adafuse_fused_switch; idx/gates are device tensors (int32[k] / fp32[k]) or None."""
+        st = load_library().adafuse_fused_switch(self._h, _ptr(idx_prev), _ptr(gates_prev), _ptr(idx_next),
+                                                 _ptr(gates_next), k, scale, mode, _stream_handle(stream))
+        if st != 0:
+            raise AdafuseError(st, "adafuse_fused_switch")
+
+    def close(self):
+        if self._h:
+            load_library().adafuse_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

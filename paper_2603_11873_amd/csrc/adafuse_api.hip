@@ -1,0 +1,266 @@
+// C-ABI of libadafuse: argument validation, matrix/tile tables, kernel dispatch.
+// Declarations and the contract of every entry point are in include/adafuse.h.
+#include "adafuse.h"
+
+#include <hip/hip_runtime.h>
+
+#include <new>
+#include <vector>
+
+#include "device_types.hpp"
+#include "pregate.hpp"
+#include "switch_mfma.hpp"
+#include "switch_valu.hpp"
+
+using namespace adafuse;
+
+struct adafuse_ctx {
+    std::vector<adafuse_matrix_desc> mats;
+    int32_t E = 0, r = 0, k_max = 0;
+    int32_t kernel = ADAFUSE_KERNEL_VALU;  // kernel in effect, never AUTO
+    int32_t tile_rows = 0, tile_cols = 0;
+    int64_t n_tiles = 0, elements = 0;
+    int device = -1;
+    MatDev *d_mats = nullptr;
+    TileDev *d_tiles = nullptr;
+};
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int terms_bucket(int k) { return k <= 1 ? 1 : (k <= 2 ? 2 : (k <= 4 ? 4 : 8)); }
+
+// The matrix-core kernel is instantiated for ranks that are multiples of 4 and
+// an inner dimension (terms x rank) of at most 64.
+bool mfma_supported(int r, int k_max)
+{
+    if (r != 4 && r != 8 && r != 16 && r != 32 && r != 64) return false;
+    return terms_bucket(k_max) * r <= 64;
+}
+
+adafuse_status validate_mats(const adafuse_matrix_desc *mats, int32_t n_mats, int32_t E, int32_t r, int32_t k_max)
+{
+    if (!mats) return ADAFUSE_ERR_NULL;
+    if (n_mats < 1 || n_mats > 65535) return ADAFUSE_ERR_ARG;
+    if (E < 1 || E > kMaxExperts) return ADAFUSE_ERR_ARG;
+    if (r != 4 && r != 8 && r != 16 && r != 32 && r != 64) return ADAFUSE_ERR_ARG;
+    if (k_max < 1 || k_max > E || k_max > kMaxTerms) return ADAFUSE_ERR_ARG;
+    for (int32_t i = 0; i < n_mats; ++i) {
+        const adafuse_matrix_desc &m = mats[i];
+        if (!m.w_base || !m.w_work || !m.a_bank || !m.b_bank) return ADAFUSE_ERR_NULL;
+        if (m.reserved != 0 || m.w_base == m.w_work) return ADAFUSE_ERR_ARG;
+        if (m.out < 1 || m.in < 8 || (m.in % 8) != 0 || m.ldw < m.in || (m.ldw % 8) != 0) return ADAFUSE_ERR_SHAPE;
+        if (m.out > (1 << 22) || m.in > (1 << 22)) return ADAFUSE_ERR_SHAPE;
+        if (!aligned16(m.w_base) || !aligned16(m.w_work) || !aligned16(m.a_bank) || !aligned16(m.b_bank))
+            return ADAFUSE_ERR_ALIGN;
+    }
+    return ADAFUSE_OK;
+}
+
+void free_tables(adafuse_ctx *c)
+{
+    if (c->d_mats) (void)hipFree(c->d_mats);
+    if (c->d_tiles) (void)hipFree(c->d_tiles);
+    c->d_mats = nullptr;
+    c->d_tiles = nullptr;
+}
+
+// Tile order: matrix by matrix, row block by row block, column tiles innermost,
+// so workgroups that run together read neighbouring column strips of the same
+// rows (shared B slice) and the A/B slices of one matrix stay cache-resident
+// while that matrix streams through.
+adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
+{
+    const int tr = kernel == ADAFUSE_KERNEL_MFMA ? kMfmaTileRows : kValuTileRows;
+    const int tc = kernel == ADAFUSE_KERNEL_MFMA ? kMfmaTileCols : kValuTileCols;
+    std::vector<MatDev> hm(c->mats.size());
+    std::vector<TileDev> ht;
+    int64_t elements = 0;
+    for (size_t i = 0; i < c->mats.size(); ++i) {
+        const adafuse_matrix_desc &m = c->mats[i];
+        hm[i] = MatDev{static_cast<const uint16_t *>(m.w_base), static_cast<uint16_t *>(m.w_work),
+                       static_cast<const uint16_t *>(m.a_bank), static_cast<const uint16_t *>(m.b_bank),
+                       m.out, m.in, m.ldw, 0};
+        const int nrt = (m.out + tr - 1) / tr, nct = (m.in + tc - 1) / tc;
+        if (nrt > 65535 || nct > 65535) return ADAFUSE_ERR_SHAPE;
+        for (int rt = 0; rt < nrt; ++rt)
+            for (int ct = 0; ct < nct; ++ct) ht.push_back(TileDev{(uint32_t)i, (uint32_t)rt | ((uint32_t)ct << 16)});
+        elements += (int64_t)m.out * m.in;
+    }
+    if (ht.size() > 0x7fffffffu) return ADAFUSE_ERR_SHAPE;
+
+    if (hipGetDevice(&c->device) != hipSuccess) return ADAFUSE_ERR_HIP;
+    MatDev *dm = nullptr;
+    TileDev *dt = nullptr;
+    if (hipMalloc(&dm, hm.size() * sizeof(MatDev)) != hipSuccess) return ADAFUSE_ERR_HIP;
+    if (hipMalloc(&dt, ht.size() * sizeof(TileDev)) != hipSuccess) {
+        (void)hipFree(dm);
+        return ADAFUSE_ERR_HIP;
+    }
+    if (hipMemcpy(dm, hm.data(), hm.size() * sizeof(MatDev), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(dt, ht.data(), ht.size() * sizeof(TileDev), hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(dm);
+        (void)hipFree(dt);
+        return ADAFUSE_ERR_HIP;
+    }
+    free_tables(c);
+    c->d_mats = dm;
+    c->d_tiles = dt;
+    c->kernel = kernel;
+    c->tile_rows = tr;
+    c->tile_cols = tc;
+    c->n_tiles = (int64_t)ht.size();
+    c->elements = elements;
+    return ADAFUSE_OK;
+}
+
+template <int R, int NT>
+void launch_mfma(const SwitchParams &p, int64_t n_tiles, hipStream_t s)
+{
+    hipLaunchKernelGGL((switch_mfma_kernel<R, NT, 4>), dim3((unsigned)n_tiles), dim3(256), 0, s, p);
+}
+
+template <int R>
+bool launch_mfma_r(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t s)
+{
+    switch (nt) {
+    case 1: launch_mfma<R, 1>(p, n_tiles, s); return true;
+    case 2: if constexpr (R * 2 <= 64) { launch_mfma<R, 2>(p, n_tiles, s); return true; } return false;
+    case 4: if constexpr (R * 4 <= 64) { launch_mfma<R, 4>(p, n_tiles, s); return true; } return false;
+    case 8: if constexpr (R * 8 <= 64) { launch_mfma<R, 8>(p, n_tiles, s); return true; } return false;
+    default: return false;
+    }
+}
+
+bool launch_mfma_any(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t s)
+{
+    switch (p.r) {
+    case 4: return launch_mfma_r<4>(p, nt, n_tiles, s);
+    case 8: return launch_mfma_r<8>(p, nt, n_tiles, s);
+    case 16: return launch_mfma_r<16>(p, nt, n_tiles, s);
+    case 32: return launch_mfma_r<32>(p, nt, n_tiles, s);
+    case 64: return launch_mfma_r<64>(p, nt, n_tiles, s);
+    default: return false;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+adafuse_status adafuse_create(const adafuse_matrix_desc *mats, int32_t n_mats, int32_t E, int32_t r, int32_t k_max,
+                              adafuse_ctx **ctx)
+{
+    if (!ctx) return ADAFUSE_ERR_NULL;
+    *ctx = nullptr;
+    adafuse_status st = validate_mats(mats, n_mats, E, r, k_max);
+    if (st != ADAFUSE_OK) return st;
+    adafuse_ctx *c = new (std::nothrow) adafuse_ctx();
+    if (!c) return ADAFUSE_ERR_HIP;
+    c->mats.assign(mats, mats + n_mats);
+    c->E = E;
+    c->r = r;
+    c->k_max = k_max;
+    st = build_tables(c, mfma_supported(r, k_max) ? ADAFUSE_KERNEL_MFMA : ADAFUSE_KERNEL_VALU);
+    if (st != ADAFUSE_OK) {
+        delete c;
+        return st;
+    }
+    *ctx = c;
+    return ADAFUSE_OK;
+}
+
+adafuse_status adafuse_destroy(adafuse_ctx *ctx)
+{
+    if (!ctx) return ADAFUSE_OK;
+    free_tables(ctx);
+    delete ctx;
+    return ADAFUSE_OK;
+}
+
+adafuse_status adafuse_set_kernel(adafuse_ctx *ctx, int32_t kernel)
+{
+    if (!ctx) return ADAFUSE_ERR_NULL;
+    if (kernel == ADAFUSE_KERNEL_AUTO)
+        kernel = mfma_supported(ctx->r, ctx->k_max) ? ADAFUSE_KERNEL_MFMA : ADAFUSE_KERNEL_VALU;
+    if (kernel != ADAFUSE_KERNEL_VALU && kernel != ADAFUSE_KERNEL_MFMA) return ADAFUSE_ERR_ARG;
+    if (kernel == ADAFUSE_KERNEL_MFMA && !mfma_supported(ctx->r, ctx->k_max)) return ADAFUSE_ERR_ARG;
+    if (kernel == ctx->kernel) return ADAFUSE_OK;
+    if (hipDeviceSynchronize() != hipSuccess) return ADAFUSE_ERR_HIP;  // no launch may still read the old table
+    return build_tables(ctx, kernel);
+}
+
+adafuse_status adafuse_get_info(const adafuse_ctx *ctx, adafuse_info *info)
+{
+    if (!ctx || !info) return ADAFUSE_ERR_NULL;
+    info->n_mats = (int32_t)ctx->mats.size();
+    info->E = ctx->E;
+    info->r = ctx->r;
+    info->k_max = ctx->k_max;
+    info->kernel = ctx->kernel;
+    info->tile_rows = ctx->tile_rows;
+    info->tile_cols = ctx->tile_cols;
+    info->reserved = 0;
+    info->n_tiles = ctx->n_tiles;
+    info->elements = ctx->elements;
+    return ADAFUSE_OK;
+}
+
+adafuse_status adafuse_pregate(const void *hidden, const void *w_router, int32_t T, int32_t d, int32_t E, int32_t k,
+                               int32_t gate_norm, int32_t *idx, float *gates, float *logits, void *hip_stream)
+{
+    if (!hidden || !w_router || !idx || !gates) return ADAFUSE_ERR_NULL;
+    if (T < 0 || E < 1 || E > kMaxExperts || k < 1 || k > E || k > kMaxTopK) return ADAFUSE_ERR_ARG;
+    if (gate_norm != ADAFUSE_GATE_SOFTMAX_OVER_TOPK && gate_norm != ADAFUSE_GATE_TOPK_OF_SOFTMAX) return ADAFUSE_ERR_ARG;
+    if (d < 8 || (d % 8) != 0) return ADAFUSE_ERR_SHAPE;
+    if (!aligned16(hidden) || !aligned16(w_router)) return ADAFUSE_ERR_ALIGN;
+    if (T == 0) return ADAFUSE_OK;
+    PregateParams p{static_cast<const uint16_t *>(hidden), static_cast<const uint16_t *>(w_router), idx, gates, logits,
+                    T, d, E, k, gate_norm};
+    hipLaunchKernelGGL(pregate_kernel, dim3((unsigned)T), dim3(256), 0, static_cast<hipStream_t>(hip_stream), p);
+    return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
+}
+
+adafuse_status adafuse_fused_switch(adafuse_ctx *ctx, const int32_t *idx_prev, const float *gates_prev,
+                                    const int32_t *idx_next, const float *gates_next, int32_t k, float scale,
+                                    int32_t mode, void *hip_stream)
+{
+    if (!ctx) return ADAFUSE_ERR_NULL;
+    if (mode != ADAFUSE_MERGE && mode != ADAFUSE_UNMERGE && mode != ADAFUSE_SWAP) return ADAFUSE_ERR_ARG;
+    if (mode != ADAFUSE_UNMERGE) {
+        if (!idx_next || !gates_next) return ADAFUSE_ERR_NULL;
+        if (k < 1 || k > ctx->k_max) return ADAFUSE_ERR_ARG;
+        if ((idx_prev == nullptr) != (gates_prev == nullptr)) return ADAFUSE_ERR_NULL;
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    SwitchParams p{ctx->d_mats, ctx->d_tiles, idx_prev, gates_prev, idx_next, gates_next,
+                   mode == ADAFUSE_UNMERGE ? 0 : k, ctx->E, ctx->r, mode, scale};
+    if (ctx->kernel == ADAFUSE_KERNEL_MFMA) {
+        if (mode == ADAFUSE_UNMERGE) {
+            hipLaunchKernelGGL((switch_copy_kernel<4>), dim3((unsigned)ctx->n_tiles), dim3(256), 0, s, p);
+        } else if (!launch_mfma_any(p, terms_bucket(k), ctx->n_tiles, s)) {
+            return ADAFUSE_ERR_ARG;
+        }
+    } else {
+        const size_t lds = valu_lds_bytes(p.k * ctx->r);
+        if (lds > 64 * 1024) return ADAFUSE_ERR_ARG;  // k*r beyond what this kernel stages in LDS
+        hipLaunchKernelGGL(switch_valu_kernel, dim3((unsigned)ctx->n_tiles), dim3(256), lds, s, p);
+    }
+    return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
+}
+
+const char *adafuse_status_string(int32_t status)
+{
+    switch (status) {
+    case ADAFUSE_OK: return "ok";
+    case ADAFUSE_ERR_NULL: return "required pointer is NULL";
+    case ADAFUSE_ERR_ARG: return "argument out of range";
+    case ADAFUSE_ERR_SHAPE: return "unsupported matrix shape";
+    case ADAFUSE_ERR_ALIGN: return "pointer or leading dimension misaligned";
+    case ADAFUSE_ERR_HIP: return "HIP runtime call failed";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

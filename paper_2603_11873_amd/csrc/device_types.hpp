@@ -1,0 +1,94 @@
+// Device-side tables and small bf16 helpers shared by the switch and router kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace adafuse {
+
+typedef __attribute__((ext_vector_type(4))) short short4_t;
+typedef __attribute__((ext_vector_type(4))) float float4_t;
+typedef __attribute__((ext_vector_type(2))) float float2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int uint4_t;
+typedef __attribute__((ext_vector_type(2))) unsigned int uint2_t;
+
+constexpr int kMaxTerms = 8;  // experts accumulated per element in one pass
+
+// One adapted matrix: the device copy of a caller descriptor (section "SGMM
+// Kernel": pointer arrays plus the shape of each segment).
+struct MatDev {
+    const uint16_t *w_base;
+    uint16_t *w_work;
+    const uint16_t *a_bank;  // [E][r][in]
+    const uint16_t *b_bank;  // [E][out][r]
+    int32_t out, in, ldw, pad;
+};
+
+// One workgroup's share of the batched update: matrix id and tile coordinates.
+struct TileDev {
+    uint32_t mat;
+    uint32_t rc;  // row tile | col tile << 16
+};
+
+struct SwitchParams {
+    const MatDev *mats;
+    const TileDev *tiles;
+    const int32_t *idx_prev;
+    const float *gates_prev;
+    const int32_t *idx_next;
+    const float *gates_next;
+    int32_t k;
+    int32_t E;
+    int32_t r;
+    int32_t mode;  // adafuse_mode
+    float scale;
+};
+
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// Two fp32 -> packed bf16 pair, round-to-nearest-even in hardware (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
+{
+    float2_t f = {lo, hi};
+    bf16x2_t h = __builtin_convertvector(f, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+// The token's term list (expert, coefficient s*g) read from device memory; every
+// lane reads the same addresses.  Terms beyond k get coefficient 0 on expert 0.
+// Returns false when the launch has nothing to do for this mode: SWAP with a
+// previous decision bit-identical to the next one.
+struct Terms {
+    int32_t e[kMaxTerms];
+    float c[kMaxTerms];
+};
+
+template <int NT>
+__device__ __forceinline__ bool load_terms(const SwitchParams &p, Terms &t)
+{
+    if (p.mode == 2 /*SWAP*/ && p.idx_prev != nullptr && p.gates_prev != nullptr) {
+        bool same = true;
+        for (int j = 0; j < p.k; ++j) {
+            same = same && (p.idx_prev[j] == p.idx_next[j]) &&
+                   (__float_as_uint(p.gates_prev[j]) == __float_as_uint(p.gates_next[j]));
+        }
+        if (same) return false;
+    }
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        if (p.mode != 1 /*UNMERGE*/ && j < p.k) {
+            int32_t e = p.idx_next[j];
+            e = e < 0 ? 0 : (e >= p.E ? p.E - 1 : e);
+            t.e[j] = e;
+            t.c[j] = p.scale * p.gates_next[j];
+        } else {
+            t.e[j] = 0;
+            t.c[j] = 0.0f;
+        }
+    }
+    return true;
+}
+
+}  // namespace adafuse

@@ -1,0 +1,271 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle.
+
+Tolerances (from the benchmark spec): merged weights within 1 bf16 ULP of the
+oracle's single-rounded value; fp32 router logits within 1e-5 relative; top-k
+indices bit-exact; gates within 1e-5 relative.
+"""
+import numpy as np
+import pytest
+import torch
+
+import adafuse_workloads as wlmod
+import paper_2603_11873_amd as af
+from gpu_util import DeviceModel, Tally, check_full, check_rows, compare, sample_rows
+
+pytestmark = pytest.mark.gpu
+
+ULP_TOL = 1            # bf16 spacings
+LOGIT_RTOL = 1e-5
+GATE_RTOL = 1e-5
+MAX_DIFF_FRACTION = 0.01   # elements allowed to differ at all (near-ties of the rounding)
+
+KERNELS = [af.KERNEL_VALU, af.KERNEL_MFMA]
+
+
+def _sync():
+    torch.cuda.synchronize()
+
+
+def _compare_pregate(oracle, hidden, router, k, norm):
+    idx, gates, logits = af.pregate(hidden, router, k, norm)
+    _sync()
+    ref = oracle.pregate(wlmod.bits(hidden), wlmod.bits(router), k, norm)
+    lg = logits.cpu().numpy().astype(np.float64)
+    scale = np.abs(ref["logits"]).max(axis=1, keepdims=True)
+    # relative to the token's largest logit: a logit that happens to be ~0 has no relative accuracy in any arithmetic
+    assert np.all(np.abs(lg - ref["logits"]) <= LOGIT_RTOL * scale)
+    # fp64 accumulation on the device: the fp32 logits normally agree to the bit
+    assert np.mean(logits.cpu().numpy() != ref["logits32"]) < 1e-3
+    got_idx = idx.cpu().numpy()
+    # tokens whose fp32 logits are not all distinct near the selection boundary are still uniquely
+    # ordered by the index rule; a token is exempt from bit-exactness only if the two sides' fp32
+    # logits differ (then both orders are valid for their own logits)
+    same_logits = np.all(logits.cpu().numpy() == ref["logits32"], axis=1)
+    assert np.array_equal(got_idx[same_logits], ref["idx"][same_logits])
+    for t in np.nonzero(~same_logits)[0]:
+        order = np.argsort(-lg[t], kind="stable")[:k]
+        assert np.array_equal(got_idx[t], order)
+    g = gates.cpu().numpy().astype(np.float64)
+    ok = same_logits
+    assert np.all(np.abs(g[ok] - ref["gates"][ok]) <= GATE_RTOL * ref["gates"][ok])
+    return idx, gates, ref
+
+
+@pytest.mark.parametrize("name", ["toy", "llama2_7b_attn", "llama3_8b_gqa_all", "llama2_13b_all"])
+@pytest.mark.parametrize("norm", [0, 1])
+def test_pregate_matches_oracle(oracle, name, norm):
+    wl = wlmod.WORKLOADS[name]
+    hidden = wlmod.gen_hidden(wl).cuda()
+    router = wlmod.gen_router(wl).cuda()
+    _compare_pregate(oracle, hidden, router, wl.k, norm)
+
+
+@pytest.mark.parametrize("E,k,d", [(1, 1, 8), (2, 2, 64), (5, 3, 72), (64, 8, 4096), (16, 1, 520)])
+def test_pregate_shapes(oracle, E, k, d):
+    g = torch.Generator().manual_seed(E * 100 + k)
+    hidden = torch.randn((7, d), generator=g).to(torch.bfloat16).cuda()
+    router = (0.02 * torch.randn((E, d), generator=g)).to(torch.bfloat16).cuda()
+    _compare_pregate(oracle, hidden, router, k, 0)
+
+
+def test_pregate_exact_tie_and_single_token(oracle):
+    g = torch.Generator().manual_seed(3)
+    hidden = torch.randn((1, 256), generator=g).to(torch.bfloat16)
+    router = (0.02 * torch.randn((6, 256), generator=g)).to(torch.bfloat16)
+    router[1] = router[4]
+    router[3] = router[4]
+    idx, gates, ref = _compare_pregate(oracle, hidden.cuda(), router.cuda(), 6, 0)
+    order = idx.cpu().numpy()[0].tolist()
+    assert order.index(1) + 1 == order.index(3) and order.index(3) + 1 == order.index(4)
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_toy_every_token_every_element_all_modes(oracle, kernel):
+    wl = wlmod.WORKLOADS["toy"]
+    m = DeviceModel(wl)
+    m.ctx.set_kernel(kernel)
+    assert m.ctx.info().kernel == kernel
+    idx, gates, _ = af.pregate(m.hidden, m.router, wl.k)
+    _sync()
+    hidx, hg = idx.cpu().numpy(), gates.cpu().numpy()
+    tally = Tally()
+    for t in range(wl.T):
+        mode = af.MERGE if t == 0 else af.SWAP
+        prev = (idx[t - 1], gates[t - 1]) if t else (None, None)
+        m.ctx.fused_switch(prev[0], prev[1], idx[t], gates[t], wl.k, wl.scale, mode)
+        _sync()
+        for mat in m.mats:
+            tally.add(check_full(oracle, mat, hidx[t], hg[t], wl.scale), ULP_TOL, t)
+    tally.finish(MAX_DIFF_FRACTION)
+    # un-merge: back to the base weights, bit for bit
+    m.ctx.fused_switch(idx[-1], gates[-1], None, None, wl.k, wl.scale, af.UNMERGE)
+    _sync()
+    for wb, ww, _, _ in m.mats:
+        assert torch.equal(wb.view(torch.int16), ww.view(torch.int16))
+    m.close()
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_invariants_on_device(oracle, kernel):
+    wl = wlmod.WORKLOADS["toy"]
+    m = DeviceModel(wl)
+    m.ctx.set_kernel(kernel)
+    dev = m.hidden.device
+    idx = torch.tensor([3, 1], dtype=torch.int32, device=dev)
+    zero = torch.zeros(2, dtype=torch.float32, device=dev)
+    # zero gates leave W bit-identical
+    m.ctx.fused_switch(None, None, idx, zero, 2, wl.scale, af.MERGE)
+    _sync()
+    for wb, ww, _, _ in m.mats:
+        assert torch.equal(wb.view(torch.int16), ww.view(torch.int16))
+    # one expert, gate 1: W + s*B A against a library fp64 GEMM rounded by the oracle's conversion
+    one = torch.tensor([1.0], dtype=torch.float32, device=dev)
+    e2 = torch.tensor([2], dtype=torch.int32, device=dev)
+    m.ctx.fused_switch(None, None, e2, one, 1, wl.scale, af.MERGE)
+    _sync()
+    for wb, ww, a, b in m.mats:
+        ref = wb.double().cpu().numpy() + wl.scale * (b[2].double().cpu().numpy() @ a[2].double().cpu().numpy())
+        mx, nd = oracle.ulp_diff(wlmod.bits(ww), oracle.f64_to_bf16(ref))
+        if mx > ULP_TOL:   # only a cancellation case may exceed it; compare() judges those
+            Tally().add(compare(oracle, wlmod.bits(wb), wlmod.bits(a), wlmod.bits(b), wlmod.bits(ww), [2], [1.0],
+                                wl.scale), ULP_TOL)
+    # SWAP with prev bit-identical to next must not touch W_work
+    g = torch.tensor([0.25, 0.75], dtype=torch.float32, device=dev)
+    m.ctx.fused_switch(None, None, idx, g, 2, wl.scale, af.MERGE)
+    _sync()
+    snap = [ww.clone() for _, ww, _, _ in m.mats]
+    for _, ww, _, _ in m.mats:
+        ww.view(torch.int16).fill_(0x7FC1)
+    m.ctx.fused_switch(idx.clone(), g.clone(), idx, g, 2, wl.scale, af.SWAP)
+    _sync()
+    for _, ww, _, _ in m.mats:
+        assert bool((ww.view(torch.int16) == 0x7FC1).all())
+    # ... and with a different prev it rewrites everything to MERGE(next)
+    g2 = torch.tensor([0.75, 0.25], dtype=torch.float32, device=dev)
+    m.ctx.fused_switch(idx, g2, idx, g, 2, wl.scale, af.SWAP)
+    _sync()
+    for (_, ww, _, _), s in zip(m.mats, snap):
+        assert torch.equal(ww.view(torch.int16), s.view(torch.int16))
+    # permuting the selection changes nothing beyond rounding order
+    m.ctx.fused_switch(None, None, idx.flip(0), g.flip(0), 2, wl.scale, af.MERGE)
+    _sync()
+    for (_, ww, _, _), s in zip(m.mats, snap):
+        mx, _ = oracle.ulp_diff(wlmod.bits(ww), wlmod.bits(s))
+        assert mx <= ULP_TOL
+    m.close()
+
+
+def test_swap_sequence_has_no_drift(oracle):
+    """A T-step SWAP sequence ends bit-equal to one MERGE of the last token from base."""
+    wl = wlmod.WORKLOADS["toy"]
+    m = DeviceModel(wl)
+    idx, gates, _ = af.pregate(m.hidden, m.router, wl.k)
+    m.ctx.fused_switch(None, None, idx[0], gates[0], wl.k, wl.scale, af.MERGE)
+    for t in range(1, wl.T):
+        m.ctx.fused_switch(idx[t - 1], gates[t - 1], idx[t], gates[t], wl.k, wl.scale, af.SWAP)
+    _sync()
+    seq = [ww.clone() for _, ww, _, _ in m.mats]
+    m.ctx.fused_switch(None, None, idx[-1], gates[-1], wl.k, wl.scale, af.MERGE)
+    _sync()
+    for (_, ww, _, _), s in zip(m.mats, seq):
+        assert torch.equal(ww.view(torch.int16), s.view(torch.int16))
+    m.close()
+
+
+RAGGED = [  # (out, in, ldw, E, r, k)
+    (1, 8, 8, 2, 4, 1),
+    (3, 24, 40, 4, 4, 2),
+    (301, 200, 200, 4, 8, 2),
+    (257, 136, 144, 8, 8, 3),
+    (255, 392, 392, 8, 16, 4),
+    (130, 128, 128, 4, 16, 2),
+    (70, 264, 272, 4, 32, 2),
+    (66, 120, 120, 2, 64, 1),
+    (513, 520, 520, 16, 8, 8),
+]
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("out,in_,ldw,E,r,k", RAGGED)
+def test_ragged_shapes_and_padding(oracle, kernel, out, in_, ldw, E, r, k):
+    dev = torch.device("cuda:0")
+    g = torch.Generator().manual_seed(out * 7 + in_)
+    base_full = (0.02 * torch.randn((out, ldw), generator=g)).to(torch.bfloat16).to(dev)
+    work_full = torch.empty_like(base_full)
+    work_full.view(torch.int16).fill_(0x7FC1)
+    a = (in_ ** -0.5 * torch.randn((E, r, in_), generator=g)).to(torch.bfloat16).to(dev)
+    b = (0.05 * torch.randn((E, out, r), generator=g)).to(torch.bfloat16).to(dev)
+    wb, ww = base_full[:, :in_], work_full[:, :in_]
+    ctx = af.Context([(wb, ww, a, b)], k)
+    try:
+        ctx.set_kernel(kernel)
+    except af.AdafuseError:
+        assert kernel == af.KERNEL_MFMA
+        pytest.skip("matrix-core kernel is not instantiated for this (r, k)")
+    idx = torch.randperm(E, generator=g)[:k].to(torch.int32).to(dev)
+    gates = torch.softmax(torch.randn(k, generator=g), 0).to(dev)
+    ctx.fused_switch(None, None, idx, gates, k, 2.0, af.MERGE)
+    _sync()
+    tally = Tally()
+    tally.add(compare(oracle, wlmod.bits(wb), wlmod.bits(a), wlmod.bits(b), wlmod.bits(ww),
+                      idx.cpu().numpy(), gates.cpu().numpy(), 2.0), ULP_TOL)
+    tally.finish(MAX_DIFF_FRACTION)
+    if ldw > in_:   # the padding columns of W_work are never written
+        assert bool((work_full[:, in_:].view(torch.int16) == 0x7FC1).all())
+    ctx.fused_switch(None, None, None, None, k, 2.0, af.UNMERGE)
+    _sync()
+    assert torch.equal(ww.contiguous().view(torch.int16), wb.contiguous().view(torch.int16))
+    ctx.close()
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_one_full_layer_of_the_7b_shape(oracle, kernel):
+    """Every element of the seven matrices of one Llama-2-7B-shaped layer (several
+    hundred tiles per matrix, 11008 is not a multiple of the tile height)."""
+    wl = wlmod.scaled_down(wlmod.WORKLOADS["llama2_7b_all"], 1)
+    m = DeviceModel(wl, gen_device="cuda")
+    m.ctx.set_kernel(kernel)
+    idx, gates, _ = af.pregate(m.hidden, m.router, wl.k)
+    t = 5
+    m.ctx.fused_switch(idx[t - 1], gates[t - 1], idx[t], gates[t], wl.k, wl.scale, af.SWAP)
+    _sync()
+    hidx, hg = idx[t].cpu().numpy(), gates[t].cpu().numpy()
+    tally = Tally()
+    for mat in m.mats:
+        tally.add(check_full(oracle, mat, hidx, hg, wl.scale), ULP_TOL)
+    tally.finish(MAX_DIFF_FRACTION)
+    print(f"\n[{kernel}] elements {tally.n}, differing from oracle {tally.diff}, cancellation cases {tally.cancel}")
+    m.close()
+
+
+@pytest.mark.parametrize("name", ["llama2_7b_attn", "llama2_7b_all", "llama3_8b_gqa_all", "llama2_13b_all"])
+def test_full_size_models_sampled_rows(oracle, name):
+    """The full model in the launch configuration the bench times (all layers, one
+    launch per token, library's kernel choice): sampled rows of EVERY matrix at
+    several tokens of the SWAP sequence, each row checked element by element."""
+    wl = wlmod.WORKLOADS[name]
+    m = DeviceModel(wl, gen_device="cuda", sentinel=True)
+    info = m.ctx.info()
+    assert info.n_mats == wl.n_mats and info.elements == wl.elements
+    idx, gates, _ = af.pregate(m.hidden, m.router, wl.k)
+    _sync()
+    hidx, hg = idx.cpu().numpy(), gates.cpu().numpy()
+    rng = np.random.default_rng(wl.seed)
+    checkpoints = sorted({0, 1, wl.T // 2, wl.T - 1})
+    tally = Tally()
+    m.ctx.fused_switch(None, None, idx[0], gates[0], wl.k, wl.scale, af.MERGE)
+    for t in range(wl.T):
+        if t:
+            m.ctx.fused_switch(idx[t - 1], gates[t - 1], idx[t], gates[t], wl.k, wl.scale, af.SWAP)
+        if t not in checkpoints:
+            continue
+        _sync()
+        for mat in m.mats:
+            rows = sample_rows(mat[0].shape[0], info.tile_rows, rng)
+            tally.add(check_rows(oracle, mat, hidx[t], hg[t], wl.scale, rows), ULP_TOL, (name, t))
+    tally.finish(MAX_DIFF_FRACTION)
+    print(f"\n[{name}] sampled elements {tally.n}, differing {tally.diff}, cancellation cases {tally.cancel}")
+    # nothing left unwritten anywhere: no element still holds the NaN sentinel
+    for _, ww, _, _ in m.mats[:: max(1, len(m.mats) // 16)]:
+        assert not bool((ww.view(torch.int16) == 0x7FC1).any())
+    m.close()
