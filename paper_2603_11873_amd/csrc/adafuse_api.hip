@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
 #include <new>
 #include <vector>
 
@@ -19,6 +20,7 @@ struct adafuse_ctx {
     int32_t E = 0, r = 0, k_max = 0;
     int32_t kernel = ADAFUSE_KERNEL_VALU;  // kernel in effect, never AUTO
     int32_t tile_rows = 0, tile_cols = 0;
+    int32_t mfma_shape = 0;  // index into the matrix-core kernel's tile shapes
     int64_t n_tiles = 0, elements = 0;
     int device = -1;
     MatDev *d_mats = nullptr;
@@ -58,6 +60,94 @@ adafuse_status validate_mats(const adafuse_matrix_desc *mats, int32_t n_mats, in
     return ADAFUSE_OK;
 }
 
+// Tile shapes the matrix-core kernel is built for: rows, waves side by side, row groups in flight.
+using Shape0 = TileShape<256, 1, 4>;
+using Shape1 = TileShape<64, 4, 4>;
+using Shape2 = TileShape<32, 4, 4>;
+using Shape3 = TileShape<16, 4, 4>;
+using Shape4 = TileShape<16, 4, 2>;
+using Shape5 = TileShape<64, 1, 4>;
+using Shape6 = TileShape<32, 2, 4>;
+using Shape7 = TileShape<128, 4, 4>;
+using Shape8 = TileShape<8, 4, 2>;
+constexpr int kNumShapes = 9;
+
+template <class F>
+bool with_shape(int shape, F &&f)
+{
+    switch (shape) {
+    case 0: return f(Shape0{});
+    case 1: return f(Shape1{});
+    case 2: return f(Shape2{});
+    case 3: return f(Shape3{});
+    case 4: return f(Shape4{});
+    case 5: return f(Shape5{});
+    case 6: return f(Shape6{});
+    case 7: return f(Shape7{});
+    case 8: return f(Shape8{});
+    default: return false;
+    }
+}
+
+template <int R, int NT, class S>
+bool launch_mfma(const SwitchParams &p, int64_t n_tiles, hipStream_t s)
+{
+    if constexpr (R * NT <= 64 && mfma_shape_fits<R, NT, S>()) {
+        hipLaunchKernelGGL((switch_mfma_kernel<R, NT, S>), dim3((unsigned)n_tiles), dim3(256), 0, s, p);
+        return true;
+    } else {
+        return false;
+    }
+}
+
+template <int R, class S>
+bool launch_mfma_r(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t s)
+{
+    switch (nt) {
+    case 1: return launch_mfma<R, 1, S>(p, n_tiles, s);
+    case 2: return launch_mfma<R, 2, S>(p, n_tiles, s);
+    case 4: return launch_mfma<R, 4, S>(p, n_tiles, s);
+    case 8: return launch_mfma<R, 8, S>(p, n_tiles, s);
+    default: return false;
+    }
+}
+
+template <class S>
+bool launch_mfma_any(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t s)
+{
+    switch (p.r) {
+    case 4: return launch_mfma_r<4, S>(p, nt, n_tiles, s);
+    case 8: return launch_mfma_r<8, S>(p, nt, n_tiles, s);
+    case 16: return launch_mfma_r<16, S>(p, nt, n_tiles, s);
+    case 32: return launch_mfma_r<32, S>(p, nt, n_tiles, s);
+    case 64: return launch_mfma_r<64, S>(p, nt, n_tiles, s);
+    default: return false;
+    }
+}
+
+// Does the LDS footprint of (r, terms) fit this tile shape?
+bool shape_fits(int shape, int r, int nt)
+{
+    const size_t kr = (size_t)r * nt;
+    return with_shape(shape, [&](auto sh) {
+        using S = decltype(sh);
+        return (size_t)S::TR * (kr + 4) * 2 <= 64 * 1024;
+    });
+}
+
+// Tile shape for a context: a tuning override from the environment
+// (ADAFUSE_MFMA_SHAPE=<index>), else the default, else the first shape that fits.
+int pick_shape(int r, int k_max)
+{
+    const int nt = terms_bucket(k_max);
+    int want = 6;  // 32 x 256: best measured on the Llama-2-7B all-linear shapes
+    if (const char *e = std::getenv("ADAFUSE_MFMA_SHAPE")) want = std::atoi(e);
+    if (want >= 0 && want < kNumShapes && shape_fits(want, r, nt)) return want;
+    for (int sh = 0; sh < kNumShapes; ++sh)
+        if (shape_fits(sh, r, nt)) return sh;
+    return 0;
+}
+
 void free_tables(adafuse_ctx *c)
 {
     if (c->d_mats) (void)hipFree(c->d_mats);
@@ -72,8 +162,15 @@ void free_tables(adafuse_ctx *c)
 // while that matrix streams through.
 adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
 {
-    const int tr = kernel == ADAFUSE_KERNEL_MFMA ? kMfmaTileRows : kValuTileRows;
-    const int tc = kernel == ADAFUSE_KERNEL_MFMA ? kMfmaTileCols : kValuTileCols;
+    int tr = kValuTileRows, tc = kValuTileCols;
+    if (kernel == ADAFUSE_KERNEL_MFMA) {
+        c->mfma_shape = pick_shape(c->r, c->k_max);
+        with_shape(c->mfma_shape, [&](auto sh) {
+            tr = decltype(sh)::TR;
+            tc = decltype(sh)::TC;
+            return true;
+        });
+    }
     std::vector<MatDev> hm(c->mats.size());
     std::vector<TileDev> ht;
     int64_t elements = 0;
@@ -113,36 +210,6 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
     c->n_tiles = (int64_t)ht.size();
     c->elements = elements;
     return ADAFUSE_OK;
-}
-
-template <int R, int NT>
-void launch_mfma(const SwitchParams &p, int64_t n_tiles, hipStream_t s)
-{
-    hipLaunchKernelGGL((switch_mfma_kernel<R, NT, 4>), dim3((unsigned)n_tiles), dim3(256), 0, s, p);
-}
-
-template <int R>
-bool launch_mfma_r(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t s)
-{
-    switch (nt) {
-    case 1: launch_mfma<R, 1>(p, n_tiles, s); return true;
-    case 2: if constexpr (R * 2 <= 64) { launch_mfma<R, 2>(p, n_tiles, s); return true; } return false;
-    case 4: if constexpr (R * 4 <= 64) { launch_mfma<R, 4>(p, n_tiles, s); return true; } return false;
-    case 8: if constexpr (R * 8 <= 64) { launch_mfma<R, 8>(p, n_tiles, s); return true; } return false;
-    default: return false;
-    }
-}
-
-bool launch_mfma_any(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t s)
-{
-    switch (p.r) {
-    case 4: return launch_mfma_r<4>(p, nt, n_tiles, s);
-    case 8: return launch_mfma_r<8>(p, nt, n_tiles, s);
-    case 16: return launch_mfma_r<16>(p, nt, n_tiles, s);
-    case 32: return launch_mfma_r<32>(p, nt, n_tiles, s);
-    case 64: return launch_mfma_r<64>(p, nt, n_tiles, s);
-    default: return false;
-    }
 }
 
 }  // namespace
@@ -237,11 +304,16 @@ adafuse_status adafuse_fused_switch(adafuse_ctx *ctx, const int32_t *idx_prev, c
     SwitchParams p{ctx->d_mats, ctx->d_tiles, idx_prev, gates_prev, idx_next, gates_next,
                    mode == ADAFUSE_UNMERGE ? 0 : k, ctx->E, ctx->r, mode, scale};
     if (ctx->kernel == ADAFUSE_KERNEL_MFMA) {
-        if (mode == ADAFUSE_UNMERGE) {
-            hipLaunchKernelGGL((switch_copy_kernel<4>), dim3((unsigned)ctx->n_tiles), dim3(256), 0, s, p);
-        } else if (!launch_mfma_any(p, terms_bucket(k), ctx->n_tiles, s)) {
-            return ADAFUSE_ERR_ARG;
-        }
+        const int64_t n_tiles = ctx->n_tiles;
+        const bool launched = with_shape(ctx->mfma_shape, [&](auto sh) {
+            using S = decltype(sh);
+            if (mode == ADAFUSE_UNMERGE) {
+                hipLaunchKernelGGL((switch_copy_kernel<S>), dim3((unsigned)n_tiles), dim3(256), 0, s, p);
+                return true;
+            }
+            return launch_mfma_any<S>(p, terms_bucket(k), n_tiles, s);
+        });
+        if (!launched) return ADAFUSE_ERR_ARG;
     } else {
         const size_t lds = valu_lds_bytes(p.k * ctx->r);
         if (lds > 64 * 1024) return ADAFUSE_ERR_ARG;  // k*r beyond what this kernel stages in LDS

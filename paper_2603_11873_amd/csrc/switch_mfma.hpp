@@ -2,7 +2,8 @@
 // P_j = B_{e_j} A_{e_j} is formed from the unmodified bf16 operands with
 // v_mfma_f32_4x4x4_16b_bf16 (fp32 accumulate), then the element update is
 // W' = rn_bf16(W + sum_j (s g_j) P_j): one fp32 FMA per expert, W added last, a
-// single rounding to bf16.  Gates never touch a bf16 operand, so no operand is re-rounded.
+// single rounding to bf16.  Gates never touch a bf16 operand, so no operand is
+// re-rounded.
 //
 // Why the 4x4x4, 16-block shape: its result layout gives every lane 4
 // consecutive columns of one row, and the 16 blocks sit side by side along the
@@ -13,38 +14,55 @@
 // matrix cores are a small fraction of the time either way.
 //
 // Mapping (block b = lane/4, li = lane%4, set s = 0/1):
-//   src0 lane: A_e[4c..4c+3][col0 + 8b + 4s + li]   (column operand, constant per tile -> registers)
+//   src0 lane: A_e[4c..4c+3][col + 8b + 2 li + s]   (column operand, constant per tile -> registers)
 //   src1 lane: B_e[row0 + 4g + li][4c..4c+3]        (row operand, from LDS per row group g)
-//   result   : lane holds P[row0+4g+li][col0 + 8b + 4s + 0..3]
-// Workgroup = 4 waves on one TR x 128 tile; wave w takes row groups g = w, w+4, ...
-// so the workgroup walks 16 consecutive rows at a time.
+//   result   : lane holds P_s[row0+4g+li][col + 8b + 2i + s], i = 0..3
+// Set s takes the even (s=0) or odd (s=1) columns of the lane's 8, so the two
+// column operands of one rank index are the two halves of ONE aligned 32-bit
+// word of the A bank: a wave fetches them with a fully coalesced dword load
+// (256 contiguous bytes) and a byte permute packs four rank indices per operand.
+// No transposition through LDS, and no dependence between waves for A.
+// A workgroup is 4 waves on one TR x (128 WC) tile: WC waves side by side, each
+// on its own 128-column strip, 4/WC stacked; a wave walks its strip 4 rows at a
+// time, U row groups in flight.
 #pragma once
 #include "device_types.hpp"
 
 namespace adafuse {
 
-constexpr int kMfmaTileRows = 256;
-constexpr int kMfmaTileCols = 128;
-
-template <int R, int NT>
-struct MfmaLds {
-    static constexpr int KR = R * NT;
-    static constexpr int kStrideA = KR + 4;  // bf16 elements; +8 bytes keeps 8-byte reads of adjacent columns off one bank
-    static constexpr int kStrideB = KR + 4;
-    uint16_t a[kMfmaTileCols][kStrideA];  // [col][kappa]  transposed A slices
-    uint16_t b[kMfmaTileRows][kStrideB];  // [row][kappa]
+template <int TR_, int WC_, int U_>
+struct TileShape {
+    static constexpr int TR = TR_;        // tile rows
+    static constexpr int WC = WC_;        // waves side by side
+    static constexpr int U = U_;          // row groups in flight per wave
+    static constexpr int WR = 4 / WC_;    // waves stacked
+    static constexpr int TC = 128 * WC_;  // tile columns
+    static constexpr int NG = TR_ / 4;    // row groups per tile
+    static_assert(WC_ == 1 || WC_ == 2 || WC_ == 4, "4 waves per workgroup");
+    static_assert(TR_ % (4 * WR) == 0 && (NG / WR) % U_ == 0, "rows must split evenly over waves and batches");
 };
 
-template <int R, int NT, int U>
+template <int R, int NT, class S>
+struct MfmaLds {
+    static constexpr int KR = R * NT;
+    static constexpr int kStride = KR + 4;  // bf16 elements; the 8-byte pad spreads rows over LDS banks
+    uint16_t b[S::TR][kStride];             // [row][kappa]  selected B slices
+};
+
+template <int R, int NT, class S>
+constexpr bool mfma_shape_fits()
+{
+    return sizeof(MfmaLds<R, NT, S>) <= 64 * 1024;
+}
+
+template <int R, int NT, class S>
 __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
 {
     constexpr int CH = R / 4;  // 4-wide chunks of the rank
-    constexpr int TR = kMfmaTileRows, TC = kMfmaTileCols;
-    constexpr int NG = TR / 4;  // row groups per tile
+    constexpr int TR = S::TR, TC = S::TC, U = S::U, WR = S::WR, WC = S::WC, NG = S::NG;
     static_assert(R % 4 == 0 && NT >= 1 && NT <= kMaxTerms, "unsupported shape");
-    static_assert((NG / 4) % U == 0, "unroll must divide the row groups per wave");
 
-    __shared__ __align__(16) MfmaLds<R, NT> lds;
+    __shared__ __align__(16) MfmaLds<R, NT, S> lds;
 
     Terms terms;
     if (!load_terms<NT>(p, terms)) return;
@@ -55,21 +73,6 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
     const int col0 = (int)(tile.rc >> 16) * TC;
     const int tid = threadIdx.x;
 
-    // ---- stage the selected A slices, transposed to [col][kappa]
-    for (int q = tid; q < NT * R * (TC / 8); q += 256) {
-        const int kappa = q / (TC / 8);
-        const int c8 = q % (TC / 8);
-        const int j = kappa / R, rho = kappa % R;
-        const int col = col0 + c8 * 8;
-        uint4_t v = {0u, 0u, 0u, 0u};
-        if (col < m.in)
-            v = *reinterpret_cast<const uint4_t *>(m.a_bank + ((size_t)terms.e[j] * R + rho) * m.in + col);
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            lds.a[c8 * 8 + 2 * h][kappa] = (uint16_t)(v[h] & 0xffffu);
-            lds.a[c8 * 8 + 2 * h + 1][kappa] = (uint16_t)(v[h] >> 16);
-        }
-    }
     // ---- stage the selected B slices, [row][kappa], 4 bf16 (8 bytes) per item
     for (int q = tid; q < TR * NT * CH; q += 256) {
         const int row = q / (NT * CH);
@@ -84,30 +87,40 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
 
     const int lane = tid & 63;
     const int wave = tid >> 6;
+    const int wc = wave % WC, wr = wave / WC;
     const int blk = lane >> 2;
     const int li = lane & 3;
-    const int col = col0 + 8 * blk;
+    const int col = col0 + 128 * wc + 8 * blk;
     const bool col_ok = col < m.in;
 
-    // column operands, constant over the tile
+    // column operands, constant over the tile: one dword = columns (c, c+1) of one rank index
     short4_t X[NT][CH][2];
 #pragma unroll
-    for (int j = 0; j < NT; ++j)
+    for (int j = 0; j < NT; ++j) {
+        const uint16_t *arow = m.a_bank + (size_t)terms.e[j] * R * m.in + col + 2 * li;
 #pragma unroll
-        for (int c = 0; c < CH; ++c)
+        for (int c = 0; c < CH; ++c) {
+            uint32_t d[4];
 #pragma unroll
-            for (int s = 0; s < 2; ++s)
-                X[j][c][s] = *reinterpret_cast<const short4_t *>(&lds.a[8 * blk + 4 * s + li][j * R + 4 * c]);
+            for (int i = 0; i < 4; ++i)
+                d[i] = col_ok ? *reinterpret_cast<const uint32_t *>(arow + (size_t)(4 * c + i) * m.in) : 0u;
+            // even column: low halves of the four words; odd column: high halves
+            uint2_t ev = {__builtin_amdgcn_perm(d[1], d[0], 0x05040100u), __builtin_amdgcn_perm(d[3], d[2], 0x05040100u)};
+            uint2_t od = {__builtin_amdgcn_perm(d[1], d[0], 0x07060302u), __builtin_amdgcn_perm(d[3], d[2], 0x07060302u)};
+            X[j][c][0] = __builtin_bit_cast(short4_t, ev);
+            X[j][c][1] = __builtin_bit_cast(short4_t, od);
+        }
+    }
 
     const uint16_t *__restrict__ wsrc = m.w_base + (size_t)col;
     uint16_t *__restrict__ wdst = m.w_work + (size_t)col;
 
-    for (int g0 = wave; g0 < NG; g0 += 4 * U) {
+    for (int g0 = wr; g0 < NG; g0 += WR * U) {
         uint4_t w[U];
         bool ok[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int row = row0 + 4 * (g0 + 4 * u) + li;
+            const int row = row0 + 4 * (g0 + WR * u) + li;
             ok[u] = col_ok && row < m.out;
             w[u] = uint4_t{0u, 0u, 0u, 0u};
             if (ok[u])
@@ -115,7 +128,7 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int g = g0 + 4 * u;
+            const int g = g0 + WR * u;
             float4_t P[NT][2];
 #pragma unroll
             for (int j = 0; j < NT; ++j) {
@@ -132,11 +145,11 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
             // that last add is exact and the error stays relative to dW, not to W
             float acc[8];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] = terms.c[0] * P[0][q >> 2][q & 3];
+            for (int q = 0; q < 8; ++q) acc[q] = terms.c[0] * P[0][q & 1][q >> 1];
 #pragma unroll
             for (int j = 1; j < NT; ++j)
 #pragma unroll
-                for (int q = 0; q < 8; ++q) acc[q] = __builtin_fmaf(terms.c[j], P[j][q >> 2][q & 3], acc[q]);
+                for (int q = 0; q < 8; ++q) acc[q] = __builtin_fmaf(terms.c[j], P[j][q & 1][q >> 1], acc[q]);
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
                 acc[2 * h] += bf16_lo(w[u][h]);
@@ -155,31 +168,32 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
 
 // UNMERGE: W_work <- W_base over the same tile table and access pattern, no
 // arithmetic.  Also the practical read+write ceiling the switch is measured against.
-template <int U>
+template <class S>
 __global__ __launch_bounds__(256) void switch_copy_kernel(SwitchParams p)
 {
-    constexpr int TR = kMfmaTileRows, TC = kMfmaTileCols, NG = TR / 4;
+    constexpr int TR = S::TR, TC = S::TC, U = S::U, WR = S::WR, WC = S::WC, NG = S::NG;
     const TileDev tile = p.tiles[blockIdx.x];
     const MatDev m = p.mats[tile.mat];
     const int row0 = (int)(tile.rc & 0xffffu) * TR;
     const int col0 = (int)(tile.rc >> 16) * TC;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wc = wave % WC, wr = wave / WC;
     const int blk = lane >> 2, li = lane & 3;
-    const int col = col0 + 8 * blk;
+    const int col = col0 + 128 * wc + 8 * blk;
     if (col >= m.in) return;
     const uint16_t *__restrict__ wsrc = m.w_base + (size_t)col;
     uint16_t *__restrict__ wdst = m.w_work + (size_t)col;
-    for (int g0 = wave; g0 < NG; g0 += 4 * U) {
+    for (int g0 = wr; g0 < NG; g0 += WR * U) {
         uint4_t w[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int row = row0 + 4 * (g0 + 4 * u) + li;
+            const int row = row0 + 4 * (g0 + WR * u) + li;
             if (row < m.out)
                 w[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(wsrc + (size_t)row * m.ldw));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int row = row0 + 4 * (g0 + 4 * u) + li;
+            const int row = row0 + 4 * (g0 + WR * u) + li;
             if (row < m.out)
                 __builtin_nontemporal_store(w[u], reinterpret_cast<uint4_t *>(wdst + (size_t)row * m.ldw));
         }
