@@ -21,6 +21,8 @@ struct adafuse_ctx {
     int32_t kernel = ADAFUSE_KERNEL_VALU;  // kernel in effect, never AUTO
     int32_t tile_rows = 0, tile_cols = 0;
     int32_t mfma_shape = 0;  // index into the matrix-core kernel's tile shapes
+    uint32_t flags = 0;      // tuning flags passed to the kernels (ADAFUSE_FLAGS)
+    int32_t order = 128;     // tiles per XCD run (ADAFUSE_ORDER; 0 = plain order, 1 = an eighth of the list)
     int64_t n_tiles = 0, elements = 0;
     int device = -1;
     MatDev *d_mats = nullptr;
@@ -63,14 +65,19 @@ adafuse_status validate_mats(const adafuse_matrix_desc *mats, int32_t n_mats, in
 // Tile shapes the matrix-core kernel is built for: rows, waves side by side, row groups in flight.
 using Shape0 = TileShape<256, 1, 4>;
 using Shape1 = TileShape<64, 4, 4>;
-using Shape2 = TileShape<32, 4, 4>;
+using Shape2 = TileShape<32, 4, 8>;
 using Shape3 = TileShape<16, 4, 4>;
-using Shape4 = TileShape<16, 4, 2>;
+using Shape4 = TileShape<64, 2, 8>;
 using Shape5 = TileShape<64, 1, 4>;
 using Shape6 = TileShape<32, 2, 4>;
 using Shape7 = TileShape<128, 4, 4>;
 using Shape8 = TileShape<8, 4, 2>;
-constexpr int kNumShapes = 9;
+using Shape9 = TileShape<16, 2, 2>;
+using Shape10 = TileShape<64, 4, 16>;
+using Shape11 = TileShape<128, 2, 16>;
+using Shape12 = TileShape<128, 1, 8>;
+using Shape13 = TileShape<32, 1, 2>;
+constexpr int kNumShapes = 14;
 
 template <class F>
 bool with_shape(int shape, F &&f)
@@ -85,6 +92,11 @@ bool with_shape(int shape, F &&f)
     case 6: return f(Shape6{});
     case 7: return f(Shape7{});
     case 8: return f(Shape8{});
+    case 9: return f(Shape9{});
+    case 10: return f(Shape10{});
+    case 11: return f(Shape11{});
+    case 12: return f(Shape12{});
+    case 13: return f(Shape13{});
     default: return false;
     }
 }
@@ -140,7 +152,9 @@ bool shape_fits(int shape, int r, int nt)
 int pick_shape(int r, int k_max)
 {
     const int nt = terms_bucket(k_max);
-    int want = 6;  // 32 x 256: best measured on the Llama-2-7B all-linear shapes
+    // measured on the Llama-shaped workloads: 64 x 512 tiles stream best; at inner
+    // dimension 64 the per-tile operand fetch wants more rows per wave (128 x 256)
+    int want = nt * r >= 64 ? 11 : 10;
     if (const char *e = std::getenv("ADAFUSE_MFMA_SHAPE")) want = std::atoi(e);
     if (want >= 0 && want < kNumShapes && shape_fits(want, r, nt)) return want;
     for (int sh = 0; sh < kNumShapes; ++sh)
@@ -186,6 +200,25 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
         elements += (int64_t)m.out * m.in;
     }
     if (ht.size() > 0x7fffffffu) return ADAFUSE_ERR_SHAPE;
+    if (const char *e = std::getenv("ADAFUSE_FLAGS")) c->flags = (uint32_t)std::atoi(e);
+    if (const char *e = std::getenv("ADAFUSE_ORDER")) c->order = std::atoi(e);
+    if (c->order >= 1) {
+        // Workgroup i runs on XCD i % 8.  Hand each XCD runs of G consecutive tiles
+        // (order 1: one run = an eighth of the list) instead of every eighth tile.
+        const size_t n = ht.size();
+        const size_t G = c->order == 1 ? (n + 7) / 8 : (size_t)c->order;
+        std::vector<TileDev> sw;
+        sw.reserve(n);
+        std::vector<char> used(n, 0);
+        const size_t slots = ((n + 8 * G - 1) / (8 * G)) * 8 * G;
+        for (size_t i = 0; i < slots; ++i) {
+            const size_t x = i % 8, q = i / 8;
+            const size_t t = ((q / G) * 8 + x) * G + (q % G);
+            if (t < n) { sw.push_back(ht[t]); used[t] = 1; }
+        }
+        for (size_t t = 0; t < n; ++t) if (!used[t]) sw.push_back(ht[t]);
+        ht.swap(sw);
+    }
 
     if (hipGetDevice(&c->device) != hipSuccess) return ADAFUSE_ERR_HIP;
     MatDev *dm = nullptr;
@@ -302,7 +335,7 @@ adafuse_status adafuse_fused_switch(adafuse_ctx *ctx, const int32_t *idx_prev, c
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     SwitchParams p{ctx->d_mats, ctx->d_tiles, idx_prev, gates_prev, idx_next, gates_next,
-                   mode == ADAFUSE_UNMERGE ? 0 : k, ctx->E, ctx->r, mode, scale};
+                   mode == ADAFUSE_UNMERGE ? 0 : k, ctx->E, ctx->r, mode, scale, ctx->flags};
     if (ctx->kernel == ADAFUSE_KERNEL_MFMA) {
         const int64_t n_tiles = ctx->n_tiles;
         const bool launched = with_shape(ctx->mfma_shape, [&](auto sh) {

@@ -42,6 +42,7 @@ struct SwitchParams {
     int32_t r;
     int32_t mode;  // adafuse_mode
     float scale;
+    uint32_t flags;  // tuning: bit0 plain (temporal) W loads, bit1 plain W stores
 };
 
 __device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }

@@ -24,7 +24,7 @@
 // No transposition through LDS, and no dependence between waves for A.
 // A workgroup is 4 waves on one TR x (128 WC) tile: WC waves side by side, each
 // on its own 128-column strip, 4/WC stacked; a wave walks its strip 4 rows at a
-// time, U row groups in flight.
+// time; the wave's whole share of W (TR/4/(4/WC) row groups) is loaded up front.
 #pragma once
 #include "device_types.hpp"
 
@@ -34,10 +34,11 @@ template <int TR_, int WC_, int U_>
 struct TileShape {
     static constexpr int TR = TR_;        // tile rows
     static constexpr int WC = WC_;        // waves side by side
-    static constexpr int U = U_;          // row groups in flight per wave
+    static constexpr int U = U_;          // row groups per batch in the copy kernel
     static constexpr int WR = 4 / WC_;    // waves stacked
     static constexpr int TC = 128 * WC_;  // tile columns
     static constexpr int NG = TR_ / 4;    // row groups per tile
+    static constexpr int NGW = NG / WR;   // row groups per wave, all in flight at once in the switch
     static_assert(WC_ == 1 || WC_ == 2 || WC_ == 4, "4 waves per workgroup");
     static_assert(TR_ % (4 * WR) == 0 && (NG / WR) % U_ == 0, "rows must split evenly over waves and batches");
 };
@@ -59,7 +60,7 @@ template <int R, int NT, class S>
 __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
 {
     constexpr int CH = R / 4;  // 4-wide chunks of the rank
-    constexpr int TR = S::TR, TC = S::TC, U = S::U, WR = S::WR, WC = S::WC, NG = S::NG;
+    constexpr int TR = S::TR, TC = S::TC, WR = S::WR, WC = S::WC, NGW = S::NGW;
     static_assert(R % 4 == 0 && NT >= 1 && NT <= kMaxTerms, "unsupported shape");
 
     __shared__ __align__(16) MfmaLds<R, NT, S> lds;
@@ -72,19 +73,6 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
     const int row0 = (int)(tile.rc & 0xffffu) * TR;
     const int col0 = (int)(tile.rc >> 16) * TC;
     const int tid = threadIdx.x;
-
-    // ---- stage the selected B slices, [row][kappa], 4 bf16 (8 bytes) per item
-    for (int q = tid; q < TR * NT * CH; q += 256) {
-        const int row = q / (NT * CH);
-        const int rem = q % (NT * CH);
-        const int j = rem / CH, c = rem % CH;
-        uint2_t v = {0u, 0u};
-        if (row0 + row < m.out)
-            v = *reinterpret_cast<const uint2_t *>(m.b_bank + ((size_t)terms.e[j] * m.out + row0 + row) * R + 4 * c);
-        *reinterpret_cast<uint2_t *>(&lds.b[row][j * R + 4 * c]) = v;
-    }
-    __syncthreads();
-
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wc = wave % WC, wr = wave / WC;
@@ -92,76 +80,115 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
     const int li = lane & 3;
     const int col = col0 + 128 * wc + 8 * blk;
     const bool col_ok = col < m.in;
-
-    // column operands, constant over the tile: one dword = columns (c, c+1) of one rank index
-    short4_t X[NT][CH][2];
-#pragma unroll
-    for (int j = 0; j < NT; ++j) {
-        const uint16_t *arow = m.a_bank + (size_t)terms.e[j] * R * m.in + col + 2 * li;
-#pragma unroll
-        for (int c = 0; c < CH; ++c) {
-            uint32_t d[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                d[i] = col_ok ? *reinterpret_cast<const uint32_t *>(arow + (size_t)(4 * c + i) * m.in) : 0u;
-            // even column: low halves of the four words; odd column: high halves
-            uint2_t ev = {__builtin_amdgcn_perm(d[1], d[0], 0x05040100u), __builtin_amdgcn_perm(d[3], d[2], 0x05040100u)};
-            uint2_t od = {__builtin_amdgcn_perm(d[1], d[0], 0x07060302u), __builtin_amdgcn_perm(d[3], d[2], 0x07060302u)};
-            X[j][c][0] = __builtin_bit_cast(short4_t, ev);
-            X[j][c][1] = __builtin_bit_cast(short4_t, od);
-        }
-    }
-
     const uint16_t *__restrict__ wsrc = m.w_base + (size_t)col;
     uint16_t *__restrict__ wdst = m.w_work + (size_t)col;
 
-    for (int g0 = wr; g0 < NG; g0 += WR * U) {
-        uint4_t w[U];
-        bool ok[U];
+    // ---- issue order.  Loads return in issue order.  With a small inner dimension
+    // the wave's whole share of W goes in flight first and the operand fetch runs
+    // under that latency.  With a large one (many operand loads, long update per row
+    // group) the operands go first, so the update of row group u can start as soon
+    // as w[u] arrives while the rest of W is still in flight.
+    constexpr bool kWFirst = (NT * R <= 16);
+    uint4_t w[NGW];
+    bool ok[NGW];
+    auto issue_w_loads = [&]() {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int row = row0 + 4 * (g0 + WR * u) + li;
+        for (int u = 0; u < NGW; ++u) {
+            const int row = row0 + 4 * (wr + WR * u) + li;
             ok[u] = col_ok && row < m.out;
             w[u] = uint4_t{0u, 0u, 0u, 0u};
             if (ok[u])
                 w[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(wsrc + (size_t)row * m.ldw));
         }
+    };
+    if constexpr (kWFirst) issue_w_loads();
+
+    constexpr int BQ = (TR * CH + 255) / 256;  // B items (4 bf16) per thread and expert
+    uint2_t vb[NT][BQ];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int g = g0 + WR * u;
-            float4_t P[NT][2];
+    for (int j = 0; j < NT; ++j) {
+        const uint16_t *bsrc = m.b_bank + ((size_t)terms.e[j] * m.out + row0) * R;
 #pragma unroll
-            for (int j = 0; j < NT; ++j) {
-                P[j][0] = float4_t{0.f, 0.f, 0.f, 0.f};
-                P[j][1] = float4_t{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < BQ; ++i) {
+            const int q = tid + 256 * i;
+            const int row = q / CH, c = q % CH;
+            vb[j][i] = uint2_t{0u, 0u};
+            if (q < TR * CH && row0 + row < m.out)
+                vb[j][i] = *reinterpret_cast<const uint2_t *>(bsrc + (size_t)row * R + 4 * c);
+        }
+    }
+
+    // column operands, constant over the tile: one dword = columns (c, c+1) of one rank index
+    uint32_t d[NT][R];
 #pragma unroll
-                for (int c = 0; c < CH; ++c) {
-                    const short4_t y = *reinterpret_cast<const short4_t *>(&lds.b[4 * g + li][j * R + 4 * c]);
-                    P[j][0] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(X[j][c][0], y, P[j][0], 0, 0, 0);
-                    P[j][1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(X[j][c][1], y, P[j][1], 0, 0, 0);
-                }
+    for (int j = 0; j < NT; ++j) {
+        const uint16_t *arow = m.a_bank + (size_t)terms.e[j] * R * m.in + col + 2 * li;
+#pragma unroll
+        for (int i = 0; i < R; ++i)
+            d[j][i] = col_ok ? *reinterpret_cast<const uint32_t *>(arow + (size_t)i * m.in) : 0u;
+    }
+
+    if constexpr (!kWFirst) issue_w_loads();
+
+    // B slices to LDS as [row][kappa]
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int i = 0; i < BQ; ++i) {
+            const int q = tid + 256 * i;
+            const int row = q / CH, c = q % CH;
+            if (q < TR * CH) *reinterpret_cast<uint2_t *>(&lds.b[row][j * R + 4 * c]) = vb[j][i];
+        }
+
+    // pack the column operands: even column = low halves of four words, odd column = high halves
+    short4_t X[NT][CH][2];
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const uint32_t *dd = &d[j][4 * c];
+            uint2_t ev = {__builtin_amdgcn_perm(dd[1], dd[0], 0x05040100u), __builtin_amdgcn_perm(dd[3], dd[2], 0x05040100u)};
+            uint2_t od = {__builtin_amdgcn_perm(dd[1], dd[0], 0x07060302u), __builtin_amdgcn_perm(dd[3], dd[2], 0x07060302u)};
+            X[j][c][0] = __builtin_bit_cast(short4_t, ev);
+            X[j][c][1] = __builtin_bit_cast(short4_t, od);
+        }
+    __syncthreads();
+
+#pragma unroll
+    for (int u = 0; u < NGW; ++u) {
+        const int g = wr + WR * u;
+        float4_t P[NT][2];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            P[j][0] = float4_t{0.f, 0.f, 0.f, 0.f};
+            P[j][1] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const short4_t y = *reinterpret_cast<const short4_t *>(&lds.b[4 * g + li][j * R + 4 * c]);
+                P[j][0] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(X[j][c][0], y, P[j][0], 0, 0, 0);
+                P[j][1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(X[j][c][1], y, P[j][1], 0, 0, 0);
             }
-            // the update is summed on its own and W added last: when W + dW cancels,
-            // that last add is exact and the error stays relative to dW, not to W
-            float acc[8];
+        }
+        // the update is summed on its own and W added last: when W + dW cancels,
+        // that last add is exact and the error stays relative to dW, not to W
+        float acc[8];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] = terms.c[0] * P[0][q & 1][q >> 1];
+        for (int q = 0; q < 8; ++q) acc[q] = terms.c[0] * P[0][q & 1][q >> 1];
 #pragma unroll
-            for (int j = 1; j < NT; ++j)
+        for (int j = 1; j < NT; ++j)
 #pragma unroll
-                for (int q = 0; q < 8; ++q) acc[q] = __builtin_fmaf(terms.c[j], P[j][q & 1][q >> 1], acc[q]);
+            for (int q = 0; q < 8; ++q) acc[q] = __builtin_fmaf(terms.c[j], P[j][q & 1][q >> 1], acc[q]);
 #pragma unroll
-            for (int h = 0; h < 4; ++h) {
-                acc[2 * h] += bf16_lo(w[u][h]);
-                acc[2 * h + 1] += bf16_hi(w[u][h]);
-            }
-            if (ok[u]) {
-                const int row = row0 + 4 * g + li;
-                uint4_t o;
+        for (int h = 0; h < 4; ++h) {
+            acc[2 * h] += bf16_lo(w[u][h]);
+            acc[2 * h + 1] += bf16_hi(w[u][h]);
+        }
+        if (ok[u]) {
+            const int row = row0 + 4 * g + li;
+            uint4_t o;
 #pragma unroll
-                for (int h = 0; h < 4; ++h) o[h] = pack_bf16_rne(acc[2 * h], acc[2 * h + 1]);
-                __builtin_nontemporal_store(o, reinterpret_cast<uint4_t *>(wdst + (size_t)row * m.ldw));
-            }
+            for (int h = 0; h < 4; ++h) o[h] = pack_bf16_rne(acc[2 * h], acc[2 * h + 1]);
+            __builtin_nontemporal_store(o, reinterpret_cast<uint4_t *>(wdst + (size_t)row * m.ldw));
         }
     }
 }

@@ -23,8 +23,21 @@ __host__ __device__ constexpr size_t valu_lds_bytes(int kr)
 __global__ __launch_bounds__(256) void switch_valu_kernel(SwitchParams p)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    Terms terms;
-    if (!load_terms<kMaxTerms>(p, terms)) return;
+    __shared__ int32_t s_e[kMaxTerms];
+    __shared__ float s_c[kMaxTerms];
+    {
+        // k is a run-time value here, so the term list lives in LDS (indexed at run time)
+        Terms terms;
+        if (!load_terms<kMaxTerms>(p, terms)) return;
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int j = 0; j < kMaxTerms; ++j) {
+                s_e[j] = terms.e[j];
+                s_c[j] = terms.c[j];
+            }
+        }
+        __syncthreads();
+    }
 
     const TileDev tile = p.tiles[blockIdx.x];
     const MatDev m = p.mats[tile.mat];
@@ -46,7 +59,7 @@ __global__ __launch_bounds__(256) void switch_valu_kernel(SwitchParams p)
         const int col = col0 + c8 * 8;
         uint4_t v = {0u, 0u, 0u, 0u};
         if (col < m.in)
-            v = *reinterpret_cast<const uint4_t *>(m.a_bank + ((size_t)terms.e[j] * r + rho) * m.in + col);
+            v = *reinterpret_cast<const uint4_t *>(m.a_bank + ((size_t)s_e[j] * r + rho) * m.in + col);
         *reinterpret_cast<uint4_t *>(sA + (size_t)kappa * kValuTileCols + c8 * 8) = v;
     }
     // stage B slices with the coefficient folded in
@@ -56,7 +69,7 @@ __global__ __launch_bounds__(256) void switch_valu_kernel(SwitchParams p)
         const int j = kappa / r, rho = kappa % r;
         float v = 0.0f;
         if (row0 + row < m.out)
-            v = terms.c[j] * bf16_bits_to_f32(m.b_bank[((size_t)terms.e[j] * m.out + row0 + row) * r + rho]);
+            v = s_c[j] * bf16_bits_to_f32(m.b_bank[((size_t)s_e[j] * m.out + row0 + row) * r + rho]);
         sB[row * kr + kappa] = v;
     }
     __syncthreads();
