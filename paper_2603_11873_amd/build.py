@@ -14,6 +14,8 @@ def build(verbose: bool = False) -> str:
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            # keep the compiler from forming packed fp32 ALU ops
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # MFMA results go to ordinary VGPRs (the vector ALU consumes them next)
+           "-mllvm", "-amdgpu-mfma-vgpr-form",
            "-Wno-unused-command-line-argument",
            "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
            "-o", LIB + ".tmp"] + SOURCES

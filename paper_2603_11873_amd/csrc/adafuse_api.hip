@@ -63,21 +63,13 @@ adafuse_status validate_mats(const adafuse_matrix_desc *mats, int32_t n_mats, in
 }
 
 // Tile shapes the matrix-core kernel is built for: rows, waves side by side, row groups in flight.
-using Shape0 = TileShape<256, 1, 4>;
-using Shape1 = TileShape<64, 4, 4>;
-using Shape2 = TileShape<32, 4, 8>;
-using Shape3 = TileShape<16, 4, 4>;
-using Shape4 = TileShape<64, 2, 8>;
-using Shape5 = TileShape<64, 1, 4>;
-using Shape6 = TileShape<32, 2, 4>;
-using Shape7 = TileShape<128, 4, 4>;
-using Shape8 = TileShape<8, 4, 2>;
-using Shape9 = TileShape<16, 2, 2>;
-using Shape10 = TileShape<64, 4, 16>;
-using Shape11 = TileShape<128, 2, 16>;
-using Shape12 = TileShape<128, 1, 8>;
-using Shape13 = TileShape<32, 1, 2>;
-constexpr int kNumShapes = 14;
+using Shape0 = TileShape<64, 4>;        // 64 x 512, the wave's 16 row groups all in flight
+using Shape1 = TileShape<256, 4, 8>;    // 256 x 512, 64 row groups per wave, 8 in flight
+using Shape2 = TileShape<128, 4, 16>;   // 128 x 512, 32 row groups per wave, 16 in flight
+using Shape3 = TileShape<32, 2>;        // 32 x 256
+using Shape4 = TileShape<128, 2>;       // 128 x 256
+using Shape5 = TileShape<16, 4>;        // 16 x 512
+constexpr int kNumShapes = 6;
 
 template <class F>
 bool with_shape(int shape, F &&f)
@@ -89,14 +81,6 @@ bool with_shape(int shape, F &&f)
     case 3: return f(Shape3{});
     case 4: return f(Shape4{});
     case 5: return f(Shape5{});
-    case 6: return f(Shape6{});
-    case 7: return f(Shape7{});
-    case 8: return f(Shape8{});
-    case 9: return f(Shape9{});
-    case 10: return f(Shape10{});
-    case 11: return f(Shape11{});
-    case 12: return f(Shape12{});
-    case 13: return f(Shape13{});
     default: return false;
     }
 }
@@ -153,8 +137,9 @@ int pick_shape(int r, int k_max)
 {
     const int nt = terms_bucket(k_max);
     // measured on the Llama-shaped workloads: 64 x 512 tiles stream best; at inner
-    // dimension 64 the per-tile operand fetch wants more rows per wave (128 x 256)
-    int want = nt * r >= 64 ? 11 : 10;
+    // dimension 64 the per-tile operand fetch wants more rows per wave (256 x 512,
+    // 8 row groups in flight)
+    int want = nt * r >= 64 ? 1 : 0;
     if (const char *e = std::getenv("ADAFUSE_MFMA_SHAPE")) want = std::atoi(e);
     if (want >= 0 && want < kNumShapes && shape_fits(want, r, nt)) return want;
     for (int sh = 0; sh < kNumShapes; ++sh)

@@ -45,6 +45,27 @@ struct SwitchParams {
     uint32_t flags;  // tuning: bit0 plain (temporal) W loads, bit1 plain W stores
 };
 
+// Pointers read out of the matrix table have no known address space, and the
+// compiler would fall back to FLAT instructions, which also count against the
+// LDS counter (every LDS wait would then drain the W loads in flight).  These
+// helpers state that the memory is global.
+#define ADAFUSE_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ T ld_global(const T *p)
+{
+    return *(const ADAFUSE_GLOBAL T *)p;
+}
+template <class T>
+__device__ __forceinline__ T ld_global_nt(const T *p)
+{
+    return __builtin_nontemporal_load((const ADAFUSE_GLOBAL T *)p);
+}
+template <class T>
+__device__ __forceinline__ void st_global_nt(T v, T *p)
+{
+    __builtin_nontemporal_store(v, (ADAFUSE_GLOBAL T *)p);
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }

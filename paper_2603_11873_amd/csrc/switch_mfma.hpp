@@ -30,17 +30,18 @@
 
 namespace adafuse {
 
-template <int TR_, int WC_, int U_>
+template <int TR_, int WC_, int D_ = 0>
 struct TileShape {
     static constexpr int TR = TR_;        // tile rows
     static constexpr int WC = WC_;        // waves side by side
-    static constexpr int U = U_;          // row groups per batch in the copy kernel
     static constexpr int WR = 4 / WC_;    // waves stacked
     static constexpr int TC = 128 * WC_;  // tile columns
     static constexpr int NG = TR_ / 4;    // row groups per tile
-    static constexpr int NGW = NG / WR;   // row groups per wave, all in flight at once in the switch
+    static constexpr int NGW = NG / WR;   // row groups per wave
+    static constexpr int DW = D_ ? D_ : NGW;  // W loads a wave keeps in flight (default: its whole share)
     static_assert(WC_ == 1 || WC_ == 2 || WC_ == 4, "4 waves per workgroup");
-    static_assert(TR_ % (4 * WR) == 0 && (NG / WR) % U_ == 0, "rows must split evenly over waves and batches");
+    static_assert(TR_ % (4 * WR) == 0, "rows must split evenly over the stacked waves");
+    static_assert(NGW % DW == 0, "window must divide the wave's row groups");
 };
 
 template <int R, int NT, class S>
@@ -60,7 +61,7 @@ template <int R, int NT, class S>
 __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
 {
     constexpr int CH = R / 4;  // 4-wide chunks of the rank
-    constexpr int TR = S::TR, TC = S::TC, WR = S::WR, WC = S::WC, NGW = S::NGW;
+    constexpr int TR = S::TR, TC = S::TC, WR = S::WR, WC = S::WC, NGW = S::NGW, DW = S::DW;
     static_assert(R % 4 == 0 && NT >= 1 && NT <= kMaxTerms, "unsupported shape");
 
     __shared__ __align__(16) MfmaLds<R, NT, S> lds;
@@ -89,17 +90,17 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
     // group) the operands go first, so the update of row group u can start as soon
     // as w[u] arrives while the rest of W is still in flight.
     constexpr bool kWFirst = (NT * R <= 16);
-    uint4_t w[NGW];
-    bool ok[NGW];
+    uint4_t w[DW];
+    auto load_w = [&](int u) -> uint4_t {
+        const int row = row0 + 4 * (wr + WR * u) + li;
+        uint4_t v = {0u, 0u, 0u, 0u};
+        if (col_ok && row < m.out)
+            v = ld_global_nt(reinterpret_cast<const uint4_t *>(wsrc + (size_t)row * m.ldw));
+        return v;
+    };
     auto issue_w_loads = [&]() {
 #pragma unroll
-        for (int u = 0; u < NGW; ++u) {
-            const int row = row0 + 4 * (wr + WR * u) + li;
-            ok[u] = col_ok && row < m.out;
-            w[u] = uint4_t{0u, 0u, 0u, 0u};
-            if (ok[u])
-                w[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(wsrc + (size_t)row * m.ldw));
-        }
+        for (int i = 0; i < DW; ++i) w[i] = load_w(i);
     };
     if constexpr (kWFirst) issue_w_loads();
 
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
             const int row = q / CH, c = q % CH;
             vb[j][i] = uint2_t{0u, 0u};
             if (q < TR * CH && row0 + row < m.out)
-                vb[j][i] = *reinterpret_cast<const uint2_t *>(bsrc + (size_t)row * R + 4 * c);
+                vb[j][i] = ld_global(reinterpret_cast<const uint2_t *>(bsrc + (size_t)row * R + 4 * c));
         }
     }
 
@@ -125,7 +126,7 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
         const uint16_t *arow = m.a_bank + (size_t)terms.e[j] * R * m.in + col + 2 * li;
 #pragma unroll
         for (int i = 0; i < R; ++i)
-            d[j][i] = col_ok ? *reinterpret_cast<const uint32_t *>(arow + (size_t)i * m.in) : 0u;
+            d[j][i] = col_ok ? ld_global(reinterpret_cast<const uint32_t *>(arow + (size_t)i * m.in)) : 0u;
     }
 
     if constexpr (!kWFirst) issue_w_loads();
@@ -154,51 +155,85 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
         }
     __syncthreads();
 
-#pragma unroll
-    for (int u = 0; u < NGW; ++u) {
+    // Row groups in windows of DW: slot i is consumed, refilled with the load of
+    // row group u + DW, and only then stored, so a refill never queues behind the
+    // store of its own step and DW loads stay in flight.
+    // Row operands of row group g: NT*CH 8-byte LDS reads, issued together and one
+    // step ahead when they are few, so their latency is not paid per expert.
+    constexpr bool kPrefetchY = (NT * R <= 32);
+    short4_t ycur[NT][CH], ynxt[NT][CH];
+    auto read_y = [&](short4_t (&y)[NT][CH], int u) {
         const int g = wr + WR * u;
-        float4_t P[NT][2];
 #pragma unroll
-        for (int j = 0; j < NT; ++j) {
-            P[j][0] = float4_t{0.f, 0.f, 0.f, 0.f};
-            P[j][1] = float4_t{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < NT; ++j)
 #pragma unroll
-            for (int c = 0; c < CH; ++c) {
-                const short4_t y = *reinterpret_cast<const short4_t *>(&lds.b[4 * g + li][j * R + 4 * c]);
-                P[j][0] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(X[j][c][0], y, P[j][0], 0, 0, 0);
-                P[j][1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(X[j][c][1], y, P[j][1], 0, 0, 0);
+            for (int c = 0; c < CH; ++c)
+                y[j][c] = *reinterpret_cast<const short4_t *>(&lds.b[4 * g + li][j * R + 4 * c]);
+    };
+    if constexpr (kPrefetchY) read_y(ycur, 0);
+
+    for (int ub = 0; ub < NGW; ub += DW) {
+#pragma unroll
+        for (int i = 0; i < DW; ++i) {
+            const int u = ub + i;
+            const int g = wr + WR * u;
+            if constexpr (kPrefetchY) {
+                if (u + 1 < NGW) read_y(ynxt, u + 1);
+            } else {
+                read_y(ycur, u);
             }
-        }
-        // the update is summed on its own and W added last: when W + dW cancels,
-        // that last add is exact and the error stays relative to dW, not to W
-        float acc[8];
+            __builtin_amdgcn_sched_barrier(0);
+            float4_t P[NT][2];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) acc[q] = terms.c[0] * P[0][q & 1][q >> 1];
+            for (int j = 0; j < NT; ++j) {
+                P[j][0] = float4_t{0.f, 0.f, 0.f, 0.f};
+                P[j][1] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int j = 1; j < NT; ++j)
+                for (int c = 0; c < CH; ++c) {
+                    P[j][0] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(X[j][c][0], ycur[j][c], P[j][0], 0, 0, 0);
+                    P[j][1] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(X[j][c][1], ycur[j][c], P[j][1], 0, 0, 0);
+                }
+            }
+            if constexpr (kPrefetchY) {
 #pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q] = __builtin_fmaf(terms.c[j], P[j][q & 1][q >> 1], acc[q]);
+                for (int j = 0; j < NT; ++j)
 #pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            acc[2 * h] += bf16_lo(w[u][h]);
-            acc[2 * h + 1] += bf16_hi(w[u][h]);
-        }
-        if (ok[u]) {
-            const int row = row0 + 4 * g + li;
+                    for (int c = 0; c < CH; ++c) ycur[j][c] = ynxt[j][c];
+            }
+            // the update is summed on its own and W added last: when W + dW cancels,
+            // that last add is exact and the error stays relative to dW, not to W
+            float acc[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] = terms.c[0] * P[0][q & 1][q >> 1];
+#pragma unroll
+            for (int j = 1; j < NT; ++j)
+#pragma unroll
+                for (int q = 0; q < 8; ++q) acc[q] = __builtin_fmaf(terms.c[j], P[j][q & 1][q >> 1], acc[q]);
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                acc[2 * h] += bf16_lo(w[i][h]);
+                acc[2 * h + 1] += bf16_hi(w[i][h]);
+            }
             uint4_t o;
 #pragma unroll
             for (int h = 0; h < 4; ++h) o[h] = pack_bf16_rne(acc[2 * h], acc[2 * h + 1]);
-            __builtin_nontemporal_store(o, reinterpret_cast<uint4_t *>(wdst + (size_t)row * m.ldw));
+            if (NGW > DW && u + DW < NGW) w[i] = load_w(u + DW);
+            const int row = row0 + 4 * g + li;
+            if (col_ok && row < m.out)
+                st_global_nt(o, reinterpret_cast<uint4_t *>(wdst + (size_t)row * m.ldw));
         }
     }
 }
 
-// UNMERGE: W_work <- W_base over the same tile table and access pattern, no
-// arithmetic.  Also the practical read+write ceiling the switch is measured against.
+// UNMERGE: W_work <- W_base over the same tile table, access pattern and load
+// window, no arithmetic.  Also the practical read+write ceiling the switch is
+// measured against.
 template <class S>
 __global__ __launch_bounds__(256) void switch_copy_kernel(SwitchParams p)
 {
-    constexpr int TR = S::TR, TC = S::TC, U = S::U, WR = S::WR, WC = S::WC, NG = S::NG;
+    constexpr int TR = S::TR, TC = S::TC, WR = S::WR, WC = S::WC, NGW = S::NGW;
+    constexpr int DW = S::DW > 4 ? 4 : S::DW;  // 4 loads in flight per lane is enough without arithmetic
+    static_assert(NGW % DW == 0, "window must divide the wave's row groups");
     const TileDev tile = p.tiles[blockIdx.x];
     const MatDev m = p.mats[tile.mat];
     const int row0 = (int)(tile.rc & 0xffffu) * TR;
@@ -210,19 +245,17 @@ __global__ __launch_bounds__(256) void switch_copy_kernel(SwitchParams p)
     if (col >= m.in) return;
     const uint16_t *__restrict__ wsrc = m.w_base + (size_t)col;
     uint16_t *__restrict__ wdst = m.w_work + (size_t)col;
-    for (int g0 = wr; g0 < NG; g0 += WR * U) {
-        uint4_t w[U];
+    for (int u0 = 0; u0 < NGW; u0 += DW) {
+        uint4_t w[DW];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int row = row0 + 4 * (g0 + WR * u) + li;
-            if (row < m.out)
-                w[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(wsrc + (size_t)row * m.ldw));
+        for (int i = 0; i < DW; ++i) {
+            const int row = row0 + 4 * (wr + WR * (u0 + i)) + li;
+            if (row < m.out) w[i] = ld_global_nt(reinterpret_cast<const uint4_t *>(wsrc + (size_t)row * m.ldw));
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int row = row0 + 4 * (g0 + WR * u) + li;
-            if (row < m.out)
-                __builtin_nontemporal_store(w[u], reinterpret_cast<uint4_t *>(wdst + (size_t)row * m.ldw));
+        for (int i = 0; i < DW; ++i) {
+            const int row = row0 + 4 * (wr + WR * (u0 + i)) + li;
+            if (row < m.out) st_global_nt(w[i], reinterpret_cast<uint4_t *>(wdst + (size_t)row * m.ldw));
         }
     }
 }

@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256) void switch_valu_kernel(SwitchParams p)
         const int col = col0 + c8 * 8;
         uint4_t v = {0u, 0u, 0u, 0u};
         if (col < m.in)
-            v = *reinterpret_cast<const uint4_t *>(m.a_bank + ((size_t)s_e[j] * r + rho) * m.in + col);
+            v = ld_global(reinterpret_cast<const uint4_t *>(m.a_bank + ((size_t)s_e[j] * r + rho) * m.in + col));
         *reinterpret_cast<uint4_t *>(sA + (size_t)kappa * kValuTileCols + c8 * 8) = v;
     }
     // stage B slices with the coefficient folded in
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void switch_valu_kernel(SwitchParams p)
         const int j = kappa / r, rho = kappa % r;
         float v = 0.0f;
         if (row0 + row < m.out)
-            v = s_c[j] * bf16_bits_to_f32(m.b_bank[((size_t)s_e[j] * m.out + row0 + row) * r + rho]);
+            v = s_c[j] * bf16_bits_to_f32(ld_global(m.b_bank + ((size_t)s_e[j] * m.out + row0 + row) * r + rho));
         sB[row * kr + kappa] = v;
     }
     __syncthreads();
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void switch_valu_kernel(SwitchParams p)
         valid[i] = row < m.out;
         w[i] = uint4_t{0u, 0u, 0u, 0u};
         if (valid[i])
-            w[i] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(m.w_base + (size_t)row * m.ldw + col));
+            w[i] = ld_global_nt(reinterpret_cast<const uint4_t *>(m.w_base + (size_t)row * m.ldw + col));
 #pragma unroll
         for (int q = 0; q < 8; ++q) acc[i][q] = 0.0f;
     }
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(256) void switch_valu_kernel(SwitchParams p)
             for (int h = 0; h < 4; ++h)
                 o[h] = pack_bf16_rne(bf16_lo(w[i][h]) + acc[i][2 * h], bf16_hi(w[i][h]) + acc[i][2 * h + 1]);
         }
-        __builtin_nontemporal_store(o, reinterpret_cast<uint4_t *>(m.w_work + (size_t)row * m.ldw + col));
+        st_global_nt(o, reinterpret_cast<uint4_t *>(m.w_work + (size_t)row * m.ldw + col));
     }
 }
 
