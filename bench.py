@@ -32,6 +32,8 @@ def parse_args():
     ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--mode", default="swap", choices=["swap", "unmerge"],
                     help="unmerge times the plain W_base->W_work copy over the same tile table")
+    ap.add_argument("--inplace", action="store_true",
+                    help="paper-literal in-place update (w_work == w_base): SWAP carries 2k experts")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=1, help="layers of the model the oracle is timed on")
     return ap.parse_args()
@@ -93,7 +95,7 @@ def main():
     for layer in range(wl.layers):
         for mi in range(len(wl.mats)):
             wb = wlmod.gen_w(wl, layer, mi, "cuda")
-            mats.append((wb, torch.empty_like(wb), wlmod.gen_a_bank(wl, layer, mi, "cuda"),
+            mats.append((wb, wb if args.inplace else torch.empty_like(wb), wlmod.gen_a_bank(wl, layer, mi, "cuda"),
                          wlmod.gen_b_bank(wl, layer, mi, "cuda")))
     hidden = wlmod.gen_hidden(wl, "cuda")
     router = wlmod.gen_router(wl, "cuda")
@@ -136,6 +138,8 @@ def main():
     kernel_ms = [a.elapsed_time(b) for a, b in events]           # the switch launch alone
     avg_kernel_s = sum(kernel_ms) / len(kernel_ms) * 1e-3
     alg_bytes = wl.algorithmic_bytes if mode == af.SWAP else 4 * wl.elements
+    if args.inplace:   # the previous token's slices are read too
+        alg_bytes += wl.algorithmic_bytes - 4 * wl.elements
     achieved = alg_bytes / avg_kernel_s / 1e9
     srt = sorted(kernel_ms)
 
@@ -153,12 +157,12 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": wl.name, "layers": wl.layers, "matrices": wl.n_mats, "elements": wl.elements,
-                   "E": wl.E, "r": wl.r, "k": wl.k, "tokens": T, "scale": wl.scale, "mode": args.mode,
+                   "E": wl.E, "r": wl.r, "k": wl.k, "tokens": T, "scale": wl.scale, "mode": args.mode + ("-inplace" if args.inplace else ""),
                    "kernel": kernel_name, "tile": [info.tile_rows, info.tile_cols], "workgroups": info.n_tiles,
                    "step": "pregate(1 token) + fused_switch(all matrices), one stream"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": read_traffic(wl.name, kernel_name) if mode == af.SWAP else None,
+                     "traffic": read_traffic(wl.name, kernel_name) if mode == af.SWAP and not args.inplace else None,
                      "kernel": f"switch_{kernel_name}_kernel" if mode == af.SWAP else "switch_copy_kernel",
                      "algorithmic_bytes_per_launch": alg_bytes,
                      "kernel_us": {"mean": avg_kernel_s * 1e6, "median": srt[len(srt) // 2] * 1e3,

@@ -47,8 +47,8 @@ typedef enum {
 } adafuse_status;
 
 typedef enum {
-    ADAFUSE_MERGE = 0,   /* W_work <- rn(W_base + dW(next)); prev ignored */
-    ADAFUSE_UNMERGE = 1, /* W_work <- W_base, bit-exact; next ignored */
+    ADAFUSE_MERGE = 0,   /* add next's experts; prev ignored */
+    ADAFUSE_UNMERGE = 1, /* remove prev's experts; next ignored */
     ADAFUSE_SWAP = 2     /* remove prev, add next, in one pass (see adafuse_fused_switch) */
 } adafuse_mode;
 
@@ -67,8 +67,14 @@ typedef enum {
  * One adapted linear matrix (one entry of the pointer/shape arrays the SGMM
  * kernel takes, section "SGMM Kernel").  All pointers are DEVICE pointers, 16-byte
  * aligned, owned by the caller and must stay valid while the context lives.
- * w_base is never written.  w_work is the matrix the model's forward pass reads.
- * w_work must not overlap w_base or any bank.
+ * w_work is the matrix the model's forward pass reads.
+ * Out of place (w_work != w_base, the default way to use the library): w_base is
+ * never written and w_work is rebuilt from it on every switch; the two must not
+ * overlap.  In place (w_work == w_base, the paper's own formulation: "the addition
+ * ... is performed in place"): the one buffer is updated by adding and subtracting
+ * low-rank terms, and its bf16 rounding error accumulates from token to token.
+ * Either all matrices of a context are in place or none is.  No buffer may
+ * overlap a bank.
  */
 typedef struct {
     const void *w_base; /* bf16 [out][ldw] */
@@ -99,8 +105,10 @@ typedef struct {
  * is the only call that allocates device memory or synchronises; the tables are
  * a few bytes per tile.  E = experts per bank, r = LoRA rank (4, 8, 16, 32 or
  * 64), k_max = largest k any later call will pass (1 <= k_max <= min(E, 8)).
+ * In place, k_max <= 4 (a SWAP then carries 2 k_max experts).
  * Errors: NULL mats/ctx or NULL pointer inside a descriptor -> ERR_NULL;
- * n_mats < 1, bad E/r/k_max, reserved != 0, w_work == w_base -> ERR_ARG;
+ * n_mats < 1, bad E/r/k_max, reserved != 0, in-place and out-of-place matrices
+ * mixed -> ERR_ARG;
  * out < 1, in < 8, in % 8, ldw < in, ldw % 8 -> ERR_SHAPE; pointer not 16-byte
  * aligned -> ERR_ALIGN; HIP failure -> ERR_HIP (no context is returned).
  */
@@ -148,8 +156,14 @@ adafuse_status adafuse_pregate(const void *hidden, const void *w_router,
  *         no arithmetic.  prev, if not NULL, is only compared with next on the
  *         device: when both are bit-identical W_work already holds the result
  *         and the kernel returns without touching it.
+ * In place (w_work == w_base; Eq.7-8 as printed), with dW(x) = s * sum_j g_j B_{e_j} A_{e_j}:
+ *   MERGE   W <- rn_bf16(W + dW(next));  UNMERGE  W <- rn_bf16(W - dW(prev));
+ *   SWAP    W <- rn_bf16(W - dW(prev) + dW(next)), the signed concatenation
+ *           [-DOWN^{t-1}, DOWN^t] summed in fp32 and rounded once per call.
+ *   prev is required for UNMERGE and SWAP; a SWAP with prev bit-identical to next
+ *   is an exactly-zero update and returns without touching W.
  * Each W element is read once and written once (2 + 2 bytes); the selected A/B
- * slices are staged in LDS.  Expert indices outside [0,E) in device memory are
+ * slices are staged in registers and LDS.  Expert indices outside [0,E) in device memory are
  * clamped into range, not detected.  The call enqueues on `hip_stream` and
  * returns; no host synchronisation.
  * Errors: NULL ctx or a NULL pointer the mode needs -> ERR_NULL; bad k or mode ->

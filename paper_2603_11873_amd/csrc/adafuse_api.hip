@@ -21,7 +21,7 @@ struct adafuse_ctx {
     int32_t kernel = ADAFUSE_KERNEL_VALU;  // kernel in effect, never AUTO
     int32_t tile_rows = 0, tile_cols = 0;
     int32_t mfma_shape = 0;  // index into the matrix-core kernel's tile shapes
-    uint32_t flags = 0;      // tuning flags passed to the kernels (ADAFUSE_FLAGS)
+    bool inplace = false;    // every matrix has w_work == w_base
     int32_t order = 128;     // tiles per XCD run (ADAFUSE_ORDER; 0 = plain order, 1 = an eighth of the list)
     int64_t n_tiles = 0, elements = 0;
     int device = -1;
@@ -36,11 +36,12 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 int terms_bucket(int k) { return k <= 1 ? 1 : (k <= 2 ? 2 : (k <= 4 ? 4 : 8)); }
 
 // The matrix-core kernel is instantiated for ranks that are multiples of 4 and
-// an inner dimension (terms x rank) of at most 64.
-bool mfma_supported(int r, int k_max)
+// an inner dimension (terms x rank) of at most 128.  In place, a SWAP carries
+// the previous and the next token's experts: twice k terms.
+bool mfma_supported(int r, int max_terms)
 {
     if (r != 4 && r != 8 && r != 16 && r != 32 && r != 64) return false;
-    return terms_bucket(k_max) * r <= 64;
+    return max_terms <= kMaxTerms && terms_bucket(max_terms) * r <= 128;
 }
 
 adafuse_status validate_mats(const adafuse_matrix_desc *mats, int32_t n_mats, int32_t E, int32_t r, int32_t k_max)
@@ -53,7 +54,8 @@ adafuse_status validate_mats(const adafuse_matrix_desc *mats, int32_t n_mats, in
     for (int32_t i = 0; i < n_mats; ++i) {
         const adafuse_matrix_desc &m = mats[i];
         if (!m.w_base || !m.w_work || !m.a_bank || !m.b_bank) return ADAFUSE_ERR_NULL;
-        if (m.reserved != 0 || m.w_base == m.w_work) return ADAFUSE_ERR_ARG;
+        if (m.reserved != 0) return ADAFUSE_ERR_ARG;
+        if ((m.w_base == m.w_work) != (mats[0].w_base == mats[0].w_work)) return ADAFUSE_ERR_ARG;  // all in place or none
         if (m.out < 1 || m.in < 8 || (m.in % 8) != 0 || m.ldw < m.in || (m.ldw % 8) != 0) return ADAFUSE_ERR_SHAPE;
         if (m.out > (1 << 22) || m.in > (1 << 22)) return ADAFUSE_ERR_SHAPE;
         if (!aligned16(m.w_base) || !aligned16(m.w_work) || !aligned16(m.a_bank) || !aligned16(m.b_bank))
@@ -88,7 +90,7 @@ bool with_shape(int shape, F &&f)
 template <int R, int NT, class S>
 bool launch_mfma(const SwitchParams &p, int64_t n_tiles, hipStream_t s)
 {
-    if constexpr (R * NT <= 64 && mfma_shape_fits<R, NT, S>()) {
+    if constexpr (R * NT <= 128 && mfma_shape_fits<R, NT, S>()) {
         hipLaunchKernelGGL((switch_mfma_kernel<R, NT, S>), dim3((unsigned)n_tiles), dim3(256), 0, s, p);
         return true;
     } else {
@@ -133,9 +135,9 @@ bool shape_fits(int shape, int r, int nt)
 
 // Tile shape for a context: a tuning override from the environment
 // (ADAFUSE_MFMA_SHAPE=<index>), else the default, else the first shape that fits.
-int pick_shape(int r, int k_max)
+int pick_shape(int r, int n_terms)
 {
-    const int nt = terms_bucket(k_max);
+    const int nt = terms_bucket(n_terms);
     // measured on the Llama-shaped workloads: 64 x 512 tiles stream best; at inner
     // dimension 64 the per-tile operand fetch wants more rows per wave (256 x 512,
     // 8 row groups in flight)
@@ -146,6 +148,9 @@ int pick_shape(int r, int k_max)
         if (shape_fits(sh, r, nt)) return sh;
     return 0;
 }
+
+// Largest term count a launch of this context can carry.
+int max_terms(const adafuse_ctx *c) { return c->inplace ? 2 * c->k_max : c->k_max; }
 
 void free_tables(adafuse_ctx *c)
 {
@@ -163,7 +168,7 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
 {
     int tr = kValuTileRows, tc = kValuTileCols;
     if (kernel == ADAFUSE_KERNEL_MFMA) {
-        c->mfma_shape = pick_shape(c->r, c->k_max);
+        c->mfma_shape = pick_shape(c->r, max_terms(c));
         with_shape(c->mfma_shape, [&](auto sh) {
             tr = decltype(sh)::TR;
             tc = decltype(sh)::TC;
@@ -185,7 +190,6 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
         elements += (int64_t)m.out * m.in;
     }
     if (ht.size() > 0x7fffffffu) return ADAFUSE_ERR_SHAPE;
-    if (const char *e = std::getenv("ADAFUSE_FLAGS")) c->flags = (uint32_t)std::atoi(e);
     if (const char *e = std::getenv("ADAFUSE_ORDER")) c->order = std::atoi(e);
     if (c->order >= 1) {
         // Workgroup i runs on XCD i % 8.  Hand each XCD runs of G consecutive tiles
@@ -247,7 +251,12 @@ adafuse_status adafuse_create(const adafuse_matrix_desc *mats, int32_t n_mats, i
     c->E = E;
     c->r = r;
     c->k_max = k_max;
-    st = build_tables(c, mfma_supported(r, k_max) ? ADAFUSE_KERNEL_MFMA : ADAFUSE_KERNEL_VALU);
+    c->inplace = mats[0].w_base == mats[0].w_work;
+    if (c->inplace && 2 * k_max > kMaxTerms) {  // an in-place SWAP carries 2k terms
+        delete c;
+        return ADAFUSE_ERR_ARG;
+    }
+    st = build_tables(c, mfma_supported(r, max_terms(c)) ? ADAFUSE_KERNEL_MFMA : ADAFUSE_KERNEL_VALU);
     if (st != ADAFUSE_OK) {
         delete c;
         return st;
@@ -268,9 +277,9 @@ adafuse_status adafuse_set_kernel(adafuse_ctx *ctx, int32_t kernel)
 {
     if (!ctx) return ADAFUSE_ERR_NULL;
     if (kernel == ADAFUSE_KERNEL_AUTO)
-        kernel = mfma_supported(ctx->r, ctx->k_max) ? ADAFUSE_KERNEL_MFMA : ADAFUSE_KERNEL_VALU;
+        kernel = mfma_supported(ctx->r, max_terms(ctx)) ? ADAFUSE_KERNEL_MFMA : ADAFUSE_KERNEL_VALU;
     if (kernel != ADAFUSE_KERNEL_VALU && kernel != ADAFUSE_KERNEL_MFMA) return ADAFUSE_ERR_ARG;
-    if (kernel == ADAFUSE_KERNEL_MFMA && !mfma_supported(ctx->r, ctx->k_max)) return ADAFUSE_ERR_ARG;
+    if (kernel == ADAFUSE_KERNEL_MFMA && !mfma_supported(ctx->r, max_terms(ctx))) return ADAFUSE_ERR_ARG;
     if (kernel == ctx->kernel) return ADAFUSE_OK;
     if (hipDeviceSynchronize() != hipSuccess) return ADAFUSE_ERR_HIP;  // no launch may still read the old table
     return build_tables(ctx, kernel);
@@ -313,28 +322,31 @@ adafuse_status adafuse_fused_switch(adafuse_ctx *ctx, const int32_t *idx_prev, c
 {
     if (!ctx) return ADAFUSE_ERR_NULL;
     if (mode != ADAFUSE_MERGE && mode != ADAFUSE_UNMERGE && mode != ADAFUSE_SWAP) return ADAFUSE_ERR_ARG;
-    if (mode != ADAFUSE_UNMERGE) {
-        if (!idx_next || !gates_next) return ADAFUSE_ERR_NULL;
-        if (k < 1 || k > ctx->k_max) return ADAFUSE_ERR_ARG;
-        if ((idx_prev == nullptr) != (gates_prev == nullptr)) return ADAFUSE_ERR_NULL;
-    }
+    const bool need_next = mode != ADAFUSE_UNMERGE;
+    const bool need_prev = ctx->inplace && mode != ADAFUSE_MERGE;  // in place, removing a merge is arithmetic
+    if (need_next && (!idx_next || !gates_next)) return ADAFUSE_ERR_NULL;
+    if (need_prev && (!idx_prev || !gates_prev)) return ADAFUSE_ERR_NULL;
+    if ((idx_prev == nullptr) != (gates_prev == nullptr)) return ADAFUSE_ERR_NULL;
+    if ((need_next || need_prev) && (k < 1 || k > ctx->k_max)) return ADAFUSE_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const bool copy_only = !ctx->inplace && mode == ADAFUSE_UNMERGE;
     SwitchParams p{ctx->d_mats, ctx->d_tiles, idx_prev, gates_prev, idx_next, gates_next,
-                   mode == ADAFUSE_UNMERGE ? 0 : k, ctx->E, ctx->r, mode, scale, ctx->flags};
+                   copy_only ? 0 : k, ctx->E, ctx->r, mode, scale, ctx->inplace ? 1 : 0};
+    const int n_terms = (need_prev ? k : 0) + (need_next ? k : 0);
     if (ctx->kernel == ADAFUSE_KERNEL_MFMA) {
         const int64_t n_tiles = ctx->n_tiles;
         const bool launched = with_shape(ctx->mfma_shape, [&](auto sh) {
             using S = decltype(sh);
-            if (mode == ADAFUSE_UNMERGE) {
+            if (copy_only) {
                 hipLaunchKernelGGL((switch_copy_kernel<S>), dim3((unsigned)n_tiles), dim3(256), 0, s, p);
                 return true;
             }
-            return launch_mfma_any<S>(p, terms_bucket(k), n_tiles, s);
+            return launch_mfma_any<S>(p, terms_bucket(n_terms), n_tiles, s);
         });
         if (!launched) return ADAFUSE_ERR_ARG;
     } else {
-        const size_t lds = valu_lds_bytes(p.k * ctx->r);
-        if (lds > 64 * 1024) return ADAFUSE_ERR_ARG;  // k*r beyond what this kernel stages in LDS
+        const size_t lds = valu_lds_bytes(n_terms * ctx->r);
+        if (lds > 64 * 1024) return ADAFUSE_ERR_ARG;  // terms*r beyond what this kernel stages in LDS
         hipLaunchKernelGGL(switch_valu_kernel, dim3((unsigned)ctx->n_tiles), dim3(256), lds, s, p);
     }
     return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;

@@ -42,7 +42,7 @@ struct SwitchParams {
     int32_t r;
     int32_t mode;  // adafuse_mode
     float scale;
-    uint32_t flags;  // tuning: bit0 plain (temporal) W loads, bit1 plain W stores
+    int32_t inplace;  // 1: w_work == w_base for every matrix (paper-literal in-place update)
 };
 
 // Pointers read out of the matrix table have no known address space, and the
@@ -90,7 +90,8 @@ struct Terms {
 template <int NT>
 __device__ __forceinline__ bool load_terms(const SwitchParams &p, Terms &t)
 {
-    if (p.mode == 2 /*SWAP*/ && p.idx_prev != nullptr && p.gates_prev != nullptr) {
+    const bool have_prev = p.idx_prev != nullptr && p.gates_prev != nullptr;
+    if (p.mode == 2 /*SWAP*/ && have_prev) {
         bool same = true;
         for (int j = 0; j < p.k; ++j) {
             same = same && (p.idx_prev[j] == p.idx_next[j]) &&
@@ -98,17 +99,24 @@ __device__ __forceinline__ bool load_terms(const SwitchParams &p, Terms &t)
         }
         if (same) return false;
     }
+    // Out of place the update is built from the immutable base, so only the next
+    // token's experts enter.  In place (Eq.7-8) the previous token's experts enter
+    // first with a negative sign, then the next token's: [-DOWN^{t-1}, DOWN^t].
+    const int n_prev = (p.inplace && p.mode != 0 /*MERGE*/) ? p.k : 0;
+    const int n_next = (p.mode != 1 /*UNMERGE*/) ? p.k : 0;
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
-        if (p.mode != 1 /*UNMERGE*/ && j < p.k) {
-            int32_t e = p.idx_next[j];
-            e = e < 0 ? 0 : (e >= p.E ? p.E - 1 : e);
-            t.e[j] = e;
-            t.c[j] = p.scale * p.gates_next[j];
-        } else {
-            t.e[j] = 0;
-            t.c[j] = 0.0f;
+        int32_t e = 0;
+        float c = 0.0f;
+        if (j < n_prev) {
+            e = p.idx_prev[j];
+            c = -(p.scale * p.gates_prev[j]);
+        } else if (j < n_prev + n_next) {
+            e = p.idx_next[j - n_prev];
+            c = p.scale * p.gates_next[j - n_prev];
         }
+        t.e[j] = e < 0 ? 0 : (e >= p.E ? p.E - 1 : e);
+        t.c[j] = c;
     }
     return true;
 }

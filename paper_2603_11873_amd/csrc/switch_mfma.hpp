@@ -81,8 +81,10 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
     const int li = lane & 3;
     const int col = col0 + 128 * wc + 8 * blk;
     const bool col_ok = col < m.in;
-    const uint16_t *__restrict__ wsrc = m.w_base + (size_t)col;
-    uint16_t *__restrict__ wdst = m.w_work + (size_t)col;
+    // no restrict: in the in-place form both point at the same matrix (a lane reads
+    // its elements before it writes them, and no other lane touches them)
+    const uint16_t *wsrc = m.w_base + (size_t)col;
+    uint16_t *wdst = m.w_work + (size_t)col;
 
     // ---- issue order.  Loads return in issue order.  With a small inner dimension
     // the wave's whole share of W goes in flight first and the operand fetch runs

@@ -60,7 +60,8 @@ def test_create_rejects_bad_arguments(L):
     assert _create(L, [_desc()], E=4, k_max=5)[0] == ERR_ARG
     assert _create(L, [_desc()], E=16, k_max=9)[0] == ERR_ARG
     assert _create(L, [_desc(reserved=1)])[0] == ERR_ARG
-    assert _create(L, [_desc(ww=0x10000)])[0] == ERR_ARG          # in-place is not offered
+    assert _create(L, [_desc(ww=0x10000), _desc()])[0] == ERR_ARG  # in-place and out-of-place mixed
+    assert _create(L, [_desc(ww=0x10000)], E=16, k_max=5)[0] == ERR_ARG   # in place: 2 k_max terms at most 8
     assert _create(L, [_desc(out=0)])[0] == ERR_SHAPE
     assert _create(L, [_desc(in_=4)])[0] == ERR_SHAPE
     assert _create(L, [_desc(in_=100)])[0] == ERR_SHAPE
@@ -72,8 +73,9 @@ def test_create_rejects_bad_arguments(L):
     assert _create(L, [_desc(), _desc(out=-3)])[0] == ERR_SHAPE
 
 
-def test_valid_create_needs_a_device_or_succeeds(L):
-    st, h = _create(L, [_desc()])
+@pytest.mark.parametrize("inplace", [False, True])
+def test_valid_create_needs_a_device_or_succeeds(L, inplace):
+    st, h = _create(L, [_desc(ww=0x10000 if inplace else 0x20000)])
     assert st in (OK, ERR_HIP)       # no GPU here -> ERR_HIP, never a crash; tables only, no launch
     if st == OK:
         assert L.adafuse_destroy(h) == OK

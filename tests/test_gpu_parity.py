@@ -269,3 +269,150 @@ def test_full_size_models_sampled_rows(oracle, name):
     for _, ww, _, _ in m.mats[:: max(1, len(m.mats) // 16)]:
         assert not bool((ww.view(torch.int16) == 0x7FC1).any())
     m.close()
+
+
+# ---- the paper-literal in-place form (w_work == w_base), Eq.7-8 ----------------
+
+def _inplace_model(wl, k_max=None):
+    dev = torch.device("cuda:0")
+    mats, base = [], []
+    for layer in range(wl.layers):
+        for mi in range(len(wl.mats)):
+            wb = wlmod.gen_w(wl, layer, mi).to(dev)
+            w = wb.clone()
+            base.append(wb)
+            mats.append((w, w, wlmod.gen_a_bank(wl, layer, mi).to(dev), wlmod.gen_b_bank(wl, layer, mi).to(dev)))
+    return mats, base, af.Context(mats, k_max or wl.k)
+
+
+def _check_inplace_step(oracle, before, mat, prev, nxt, scale):
+    """One in-place call against the oracle's single-rounded Eq.8 step from the same bits."""
+    _, w, a, b = mat
+    want = oracle.inplace_swap(before, wlmod.bits(a), wlmod.bits(b), prev[0], prev[1], nxt[0], nxt[1], scale)
+    got = wlmod.bits(w)
+    mx, nd = oracle.ulp_diff(got, want)
+    if mx > ULP_TOL:
+        # only a cancellation may exceed one spacing (same derived bar as gpu_util.compare,
+        # with the previous token's terms counted too)
+        to_f = lambda x: wlmod.from_bits(x).double().numpy()
+        A, B = to_f(wlmod.bits(a)), to_f(wlmod.bits(b))
+        exact = to_f(before)
+        mag = np.abs(exact)
+        n_terms = 0
+        for sign, (ids, gs) in ((-1, prev), (1, nxt)):
+            for e, g in zip(ids, gs):
+                exact = exact + sign * scale * float(g) * (B[e] @ A[e])
+                mag = mag + abs(scale * float(g)) * (np.abs(B[e]) @ np.abs(A[e]))
+                n_terms += 1
+        gv, wv = to_f(got), to_f(want)
+        spacing = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(wv), 2.0 ** -126))) - 7)
+        line = lambda x: np.where(x.astype(np.int32) & 0x8000, -(x.astype(np.int32) & 0x7FFF), x.astype(np.int32))
+        over = np.abs(line(got) - line(want)) > ULP_TOL
+        bound = 0.5 * spacing + (a.shape[1] + n_terms + 2) * 2.0 ** -24 * mag
+        assert np.all(np.abs(gv - exact)[over] <= bound[over]), "in-place step outside both bars"
+        assert np.all(np.abs(exact)[over] < 2.0 ** -8 * mag[over])
+        assert np.count_nonzero(over) <= max(2, 1e-5 * over.size)
+    return nd, want.size
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_inplace_swap_sequence_matches_oracle_step_by_step(oracle, kernel):
+    wl = wlmod.WORKLOADS["toy"]
+    mats, base, ctx = _inplace_model(wl)
+    ctx.set_kernel(kernel)
+    hidden, router = wlmod.gen_hidden(wl).cuda(), wlmod.gen_router(wl).cuda()
+    idx, gates, _ = af.pregate(hidden, router, wl.k)
+    _sync()
+    hidx, hg = idx.cpu().numpy(), gates.cpu().numpy()
+    empty = (np.zeros(0, np.int32), np.zeros(0, np.float32))
+    diff = total = 0
+    for t in range(wl.T):
+        before = [wlmod.bits(m[1]) for m in mats]
+        if t == 0:
+            ctx.fused_switch(None, None, idx[0], gates[0], wl.k, wl.scale, af.MERGE)
+            prev = empty
+        else:
+            ctx.fused_switch(idx[t - 1], gates[t - 1], idx[t], gates[t], wl.k, wl.scale, af.SWAP)
+            prev = (hidx[t - 1], hg[t - 1])
+        _sync()
+        for mat, bf in zip(mats, before):
+            nd, n = _check_inplace_step(oracle, bf, mat, prev, (hidx[t], hg[t]), wl.scale)
+            diff += nd
+            total += n
+    assert diff <= MAX_DIFF_FRACTION * total
+    # drift: the in-place weights against the drift-free definition W_base + dW(last token),
+    # in units of the spacing at the base weight's magnitude (the spacing of the
+    # result itself is meaningless where the result is near zero)
+    worst = 0.0
+    n_off = n_all = 0
+    for mat, wb in zip(mats, base):
+        want = oracle.merge(wlmod.bits(wb), wlmod.bits(mat[2]), wlmod.bits(mat[3]), hidx[-1], hg[-1], wl.scale)
+        gv = mat[1].double().cpu().numpy()
+        wv = wlmod.from_bits(want).double().numpy()
+        bv = np.abs(wb.double().cpu().numpy())
+        sp = 2.0 ** (np.floor(np.log2(np.maximum(np.maximum(bv, np.abs(wv)), 2.0 ** -126))) - 7)
+        worst = max(worst, float(np.max(np.abs(gv - wv) / sp)))
+        n_off += int(np.count_nonzero(gv != wv))
+        n_all += gv.size
+    print(f"\n[kernel {kernel}] in-place drift after {wl.T} tokens: {n_off / n_all:.1%} of the elements differ from the "
+          f"stateless result, by up to {worst:.2f} spacings of the base weight")
+    assert worst >= 1          # it does drift; that is why out of place is the default
+    # un-merge in place: arithmetic, so W_base only up to the accumulated rounding
+    before = [wlmod.bits(m[1]) for m in mats]
+    ctx.fused_switch(idx[-1], gates[-1], None, None, wl.k, wl.scale, af.UNMERGE)
+    _sync()
+    for mat, bf in zip(mats, before):
+        _check_inplace_step(oracle, bf, mat, (hidx[-1], hg[-1]), empty, wl.scale)
+    # same decision twice: exactly-zero update, W untouched
+    snap = [m[1].clone() for m in mats]
+    ctx.fused_switch(idx[3], gates[3], idx[3].clone(), gates[3].clone(), wl.k, wl.scale, af.SWAP)
+    _sync()
+    for mat, s in zip(mats, snap):
+        assert torch.equal(mat[1].view(torch.int16), s.view(torch.int16))
+    ctx.close()
+
+
+def test_inplace_needs_prev_and_rejects_large_k():
+    wl = wlmod.WORKLOADS["toy"]
+    mats, _, ctx = _inplace_model(wl)
+    dev = mats[0][0].device
+    idx = torch.tensor([0, 1], dtype=torch.int32, device=dev)
+    g = torch.tensor([0.5, 0.5], dtype=torch.float32, device=dev)
+    with pytest.raises(af.AdafuseError):
+        ctx.fused_switch(None, None, idx, g, 2, 2.0, af.SWAP)
+    with pytest.raises(af.AdafuseError):
+        ctx.fused_switch(None, None, None, None, 2, 2.0, af.UNMERGE)
+    ctx.close()
+
+
+def test_inplace_full_layer_7b_shape(oracle):
+    """In-place SWAP on one Llama-2-7B-shaped layer (4 terms of rank 8 per element)."""
+    wl = wlmod.scaled_down(wlmod.WORKLOADS["llama2_7b_all"], 1)
+    dev = torch.device("cuda:0")
+    mats = []
+    for mi in range(len(wl.mats)):
+        w = wlmod.gen_w(wl, 0, mi, "cuda")
+        mats.append((w, w, wlmod.gen_a_bank(wl, 0, mi, "cuda"), wlmod.gen_b_bank(wl, 0, mi, "cuda")))
+    ctx = af.Context(mats, wl.k)
+    hidden, router = wlmod.gen_hidden(wl, "cuda"), wlmod.gen_router(wl, "cuda")
+    idx, gates, _ = af.pregate(hidden, router, wl.k)
+    ctx.fused_switch(None, None, idx[0], gates[0], wl.k, wl.scale, af.MERGE)
+    _sync()
+    hidx, hg = idx.cpu().numpy(), gates.cpu().numpy()
+    rng = np.random.default_rng(1)
+    rows = {mi: sample_rows(m[0].shape[0], 64, rng) for mi, m in enumerate(mats)}
+    before = {}
+    for mi, m in enumerate(mats):
+        ridx = torch.as_tensor(rows[mi], device=dev)
+        before[mi] = wlmod.bits(m[1].index_select(0, ridx))
+    ctx.fused_switch(idx[0], gates[0], idx[1], gates[1], wl.k, wl.scale, af.SWAP)
+    _sync()
+    diff = total = 0
+    for mi, m in enumerate(mats):
+        ridx = torch.as_tensor(rows[mi], device=dev)
+        sub = (None, m[1].index_select(0, ridx), m[2], m[3].index_select(1, ridx))
+        nd, n = _check_inplace_step(oracle, before[mi], sub, (hidx[0], hg[0]), (hidx[1], hg[1]), wl.scale)
+        diff += nd
+        total += n
+    assert diff <= MAX_DIFF_FRACTION * total
+    ctx.close()
