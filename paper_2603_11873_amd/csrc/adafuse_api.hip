@@ -184,9 +184,13 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
                        static_cast<const uint16_t *>(m.a_bank), static_cast<const uint16_t *>(m.b_bank),
                        m.out, m.in, m.ldw, 0};
         const int nrt = (m.out + tr - 1) / tr, nct = (m.in + tc - 1) / tc;
-        if (nrt > 65535 || nct > 65535) return ADAFUSE_ERR_SHAPE;
         for (int rt = 0; rt < nrt; ++rt)
-            for (int ct = 0; ct < nct; ++ct) ht.push_back(TileDev{(uint32_t)i, (uint32_t)rt | ((uint32_t)ct << 16)});
+            for (int ct = 0; ct < nct; ++ct) {
+                const int row0 = rt * tr, col0 = ct * tc;
+                const size_t off = (size_t)row0 * m.ldw + col0;
+                ht.push_back(TileDev{hm[i].w_base + off, hm[i].w_work + off, (uint32_t)i, row0, col0, m.ldw,
+                                     m.out - row0, m.in - col0});
+            }
         elements += (int64_t)m.out * m.in;
     }
     if (ht.size() > 0x7fffffffu) return ADAFUSE_ERR_SHAPE;

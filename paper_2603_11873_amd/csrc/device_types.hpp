@@ -24,10 +24,18 @@ struct MatDev {
     int32_t out, in, ldw, pad;
 };
 
-// One workgroup's share of the batched update: matrix id and tile coordinates.
+// One workgroup's share of the batched update.  The entry carries everything the
+// W loads need (tile origin in both buffers, leading dimension, bounds), so they
+// can be issued after ONE table read; the matrix table is read alongside, for
+// the operand banks only.
 struct TileDev {
+    const uint16_t *w_src;  // &W_base[row0][col0]
+    uint16_t *w_dst;        // &W_work[row0][col0]
     uint32_t mat;
-    uint32_t rc;  // row tile | col tile << 16
+    int32_t row0, col0;
+    int32_t ldw;
+    int32_t rows_left;      // out - row0
+    int32_t cols_left;      // in - col0
 };
 
 struct SwitchParams {

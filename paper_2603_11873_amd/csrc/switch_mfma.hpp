@@ -71,20 +71,22 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
 
     const TileDev tile = p.tiles[blockIdx.x];
     const MatDev m = p.mats[tile.mat];
-    const int row0 = (int)(tile.rc & 0xffffu) * TR;
-    const int col0 = (int)(tile.rc >> 16) * TC;
+    const int row0 = tile.row0;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wc = wave % WC, wr = wave / WC;
     const int blk = lane >> 2;
     const int li = lane & 3;
-    const int col = col0 + 128 * wc + 8 * blk;
-    const bool col_ok = col < m.in;
+    const int lcol = 128 * wc + 8 * blk;           // column inside the tile
+    const int col = tile.col0 + lcol;
+    const bool col_ok = lcol < tile.cols_left;
+    const int ldw = tile.ldw;
+    const int rows_left = tile.rows_left;
     // no restrict: in the in-place form both point at the same matrix (a lane reads
     // its elements before it writes them, and no other lane touches them)
-    const uint16_t *wsrc = m.w_base + (size_t)col;
-    uint16_t *wdst = m.w_work + (size_t)col;
+    const uint16_t *wsrc = tile.w_src + lcol;
+    uint16_t *wdst = tile.w_dst + lcol;
 
     // ---- issue order.  Loads return in issue order.  With a small inner dimension
     // the wave's whole share of W goes in flight first and the operand fetch runs
@@ -94,10 +96,10 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
     constexpr bool kWFirst = (NT * R <= 16);
     uint4_t w[DW];
     auto load_w = [&](int u) -> uint4_t {
-        const int row = row0 + 4 * (wr + WR * u) + li;
+        const int lrow = 4 * (wr + WR * u) + li;   // row inside the tile
         uint4_t v = {0u, 0u, 0u, 0u};
-        if (col_ok && row < m.out)
-            v = ld_global_nt(reinterpret_cast<const uint4_t *>(wsrc + (size_t)row * m.ldw));
+        if (col_ok && lrow < rows_left)
+            v = ld_global_nt(reinterpret_cast<const uint4_t *>(wsrc + (size_t)lrow * ldw));
         return v;
     };
     auto issue_w_loads = [&]() {
@@ -220,9 +222,9 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
 #pragma unroll
             for (int h = 0; h < 4; ++h) o[h] = pack_bf16_rne(acc[2 * h], acc[2 * h + 1]);
             if (NGW > DW && u + DW < NGW) w[i] = load_w(u + DW);
-            const int row = row0 + 4 * g + li;
-            if (col_ok && row < m.out)
-                st_global_nt(o, reinterpret_cast<uint4_t *>(wdst + (size_t)row * m.ldw));
+            const int lrow = 4 * g + li;
+            if (col_ok && lrow < rows_left)
+                st_global_nt(o, reinterpret_cast<uint4_t *>(wdst + (size_t)lrow * ldw));
         }
     }
 }
@@ -233,31 +235,29 @@ __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
 template <class S>
 __global__ __launch_bounds__(256) void switch_copy_kernel(SwitchParams p)
 {
-    constexpr int TR = S::TR, TC = S::TC, WR = S::WR, WC = S::WC, NGW = S::NGW;
+    constexpr int WR = S::WR, WC = S::WC, NGW = S::NGW;
     constexpr int DW = S::DW > 4 ? 4 : S::DW;  // 4 loads in flight per lane is enough without arithmetic
     static_assert(NGW % DW == 0, "window must divide the wave's row groups");
     const TileDev tile = p.tiles[blockIdx.x];
-    const MatDev m = p.mats[tile.mat];
-    const int row0 = (int)(tile.rc & 0xffffu) * TR;
-    const int col0 = (int)(tile.rc >> 16) * TC;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wc = wave % WC, wr = wave / WC;
     const int blk = lane >> 2, li = lane & 3;
-    const int col = col0 + 128 * wc + 8 * blk;
-    if (col >= m.in) return;
-    const uint16_t *__restrict__ wsrc = m.w_base + (size_t)col;
-    uint16_t *__restrict__ wdst = m.w_work + (size_t)col;
+    const int lcol = 128 * wc + 8 * blk;
+    if (lcol >= tile.cols_left) return;
+    const uint16_t *__restrict__ wsrc = tile.w_src + lcol;
+    uint16_t *__restrict__ wdst = tile.w_dst + lcol;
+    const int ldw = tile.ldw, rows_left = tile.rows_left;
     for (int u0 = 0; u0 < NGW; u0 += DW) {
         uint4_t w[DW];
 #pragma unroll
         for (int i = 0; i < DW; ++i) {
-            const int row = row0 + 4 * (wr + WR * (u0 + i)) + li;
-            if (row < m.out) w[i] = ld_global_nt(reinterpret_cast<const uint4_t *>(wsrc + (size_t)row * m.ldw));
+            const int lrow = 4 * (wr + WR * (u0 + i)) + li;
+            if (lrow < rows_left) w[i] = ld_global_nt(reinterpret_cast<const uint4_t *>(wsrc + (size_t)lrow * ldw));
         }
 #pragma unroll
         for (int i = 0; i < DW; ++i) {
-            const int row = row0 + 4 * (wr + WR * (u0 + i)) + li;
-            if (row < m.out) st_global_nt(w[i], reinterpret_cast<uint4_t *>(wdst + (size_t)row * m.ldw));
+            const int lrow = 4 * (wr + WR * (u0 + i)) + li;
+            if (lrow < rows_left) st_global_nt(w[i], reinterpret_cast<uint4_t *>(wdst + (size_t)lrow * ldw));
         }
     }
 }

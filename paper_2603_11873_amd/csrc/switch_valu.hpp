@@ -41,8 +41,8 @@ __global__ __launch_bounds__(256) void switch_valu_kernel(SwitchParams p)
 
     const TileDev tile = p.tiles[blockIdx.x];
     const MatDev m = p.mats[tile.mat];
-    const int row0 = (int)(tile.rc & 0xffffu) * kValuTileRows;
-    const int col0 = (int)(tile.rc >> 16) * kValuTileCols;
+    const int row0 = tile.row0;
+    const int col0 = tile.col0;
     const int nt = p.inplace ? (p.mode == 2 ? 2 * p.k : p.k) : (p.mode == 1 ? 0 : p.k);
     const int r = p.r;
     const int kr = nt * r;
