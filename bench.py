@@ -34,6 +34,8 @@ def parse_args():
                     help="unmerge times the plain W_base->W_work copy over the same tile table")
     ap.add_argument("--inplace", action="store_true",
                     help="paper-literal in-place update (w_work == w_base): SWAP carries 2k experts")
+    ap.add_argument("--per-matrix", action="store_true",
+                    help="the paper's 'simple merge' ablation: one launch per adapted matrix instead of one for all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=1, help="layers of the model the oracle is timed on")
     return ap.parse_args()
@@ -110,13 +112,15 @@ def main():
     stream = torch.cuda.Stream(device=dev)
     mode = af.SWAP if args.mode == "swap" else af.UNMERGE
 
+    switch = ctx.switch_per_matrix if args.per_matrix else ctx.fused_switch
+
     def step(t, ev=None):
         """Router for token t, then the fused switch from token t-1's decision to t's."""
         cur, prv = t % T, (t - 1) % T
         af.pregate(hidden[cur:cur + 1], router, wl.k, out=(idx[cur:cur + 1], gates[cur:cur + 1], None), stream=stream)
         if ev is not None:
             ev[0].record(stream)
-        ctx.fused_switch(idx[prv], gates[prv], idx[cur], gates[cur], wl.k, wl.scale, mode, stream=stream)
+        switch(idx[prv], gates[prv], idx[cur], gates[cur], wl.k, wl.scale, mode, stream=stream)
         if ev is not None:
             ev[1].record(stream)
 
@@ -157,7 +161,8 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": wl.name, "layers": wl.layers, "matrices": wl.n_mats, "elements": wl.elements,
-                   "E": wl.E, "r": wl.r, "k": wl.k, "tokens": T, "scale": wl.scale, "mode": args.mode + ("-inplace" if args.inplace else ""),
+                   "E": wl.E, "r": wl.r, "k": wl.k, "tokens": T, "scale": wl.scale, "mode": args.mode + ("-inplace" if args.inplace else "") + ("-per-matrix" if args.per_matrix else ""),
+                   "launches_per_switch": wl.n_mats if args.per_matrix else 1,
                    "kernel": kernel_name, "tile": [info.tile_rows, info.tile_cols], "workgroups": info.n_tiles,
                    "step": "pregate(1 token) + fused_switch(all matrices), one stream"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

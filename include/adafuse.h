@@ -174,6 +174,19 @@ adafuse_status adafuse_fused_switch(adafuse_ctx *ctx,
                                     const int32_t *idx_next, const float *gates_next,
                                     int32_t k, float scale, int32_t mode, void *hip_stream);
 
+/*
+ * The "simple merge" the paper measures its fused kernel against (section "SGMM
+ * Kernel", first paragraph; ablation table): the same update, same arguments,
+ * same kernels and same result as adafuse_fused_switch, but merged layer by
+ * layer -- one launch per adapted matrix, n_mats launches per call, enqueued in
+ * matrix order on `hip_stream`.  Exists to measure what the single batched
+ * launch buys; not meant for production use.
+ */
+adafuse_status adafuse_switch_per_matrix(adafuse_ctx *ctx,
+                                         const int32_t *idx_prev, const float *gates_prev,
+                                         const int32_t *idx_next, const float *gates_next,
+                                         int32_t k, float scale, int32_t mode, void *hip_stream);
+
 const char *adafuse_status_string(int32_t status);
 
 #ifdef __cplusplus

@@ -11,7 +11,7 @@ GATE_SOFTMAX_OVER_TOPK, GATE_TOPK_OF_SOFTMAX = 0, 1
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
 
 EXPORTS = ["adafuse_create", "adafuse_destroy", "adafuse_set_kernel", "adafuse_get_info",
-           "adafuse_pregate", "adafuse_fused_switch", "adafuse_status_string"]
+           "adafuse_pregate", "adafuse_fused_switch", "adafuse_switch_per_matrix", "adafuse_status_string"]
 
 
 class AdafuseError(RuntimeError):
@@ -60,6 +60,8 @@ def load_library():
     L.adafuse_pregate.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
     L.adafuse_fused_switch.restype = i32
     L.adafuse_fused_switch.argtypes = [vp, vp, vp, vp, vp, i32, f32, i32, vp]
+    L.adafuse_switch_per_matrix.restype = i32
+    L.adafuse_switch_per_matrix.argtypes = [vp, vp, vp, vp, vp, i32, f32, i32, vp]
     L.adafuse_status_string.restype = C.c_char_p
     L.adafuse_status_string.argtypes = [i32]
     _lib = L
@@ -151,6 +153,13 @@ class Context:
                                                  _ptr(gates_next), k, scale, mode, _stream_handle(stream))
         if st != 0:
             raise AdafuseError(st, "adafuse_fused_switch")
+
+    def switch_per_matrix(self, idx_prev, gates_prev, idx_next, gates_next, k, scale, mode, stream=None):
+        """adafuse_switch_per_matrix: same update, one launch per matrix (the paper's "simple merge")."""
+        st = load_library().adafuse_switch_per_matrix(self._h, _ptr(idx_prev), _ptr(gates_prev), _ptr(idx_next),
+                                                      _ptr(gates_next), k, scale, mode, _stream_handle(stream))
+        if st != 0:
+            raise AdafuseError(st, "adafuse_switch_per_matrix")
 
     def close(self):
         if self._h:

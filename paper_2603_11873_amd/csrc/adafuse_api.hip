@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
 #include <new>
 #include <vector>
@@ -26,7 +27,8 @@ struct adafuse_ctx {
     int64_t n_tiles = 0, elements = 0;
     int device = -1;
     MatDev *d_mats = nullptr;
-    TileDev *d_tiles = nullptr;
+    TileDev *d_tiles = nullptr;          // [0, n_tiles): whole model; [n_tiles, 2 n_tiles): matrix by matrix
+    std::vector<int64_t> mat_tile_off;   // per-matrix ranges inside the second section (n_mats + 1 entries)
 };
 
 namespace {
@@ -160,6 +162,29 @@ void free_tables(adafuse_ctx *c)
     c->d_tiles = nullptr;
 }
 
+// Workgroup i of a launch runs on XCD i % 8.  Reorder tiles [begin, end) so that
+// each XCD gets runs of G consecutive tiles instead of every eighth tile.
+void deal_to_xcds(std::vector<TileDev> &v, size_t begin, size_t end, size_t G)
+{
+    const size_t n = end - begin;
+    if (n == 0 || G == 0) return;
+    std::vector<TileDev> sw;
+    sw.reserve(n);
+    std::vector<char> used(n, 0);
+    const size_t slots = ((n + 8 * G - 1) / (8 * G)) * 8 * G;
+    for (size_t i = 0; i < slots; ++i) {
+        const size_t x = i % 8, q = i / 8;
+        const size_t t = ((q / G) * 8 + x) * G + (q % G);
+        if (t < n) {
+            sw.push_back(v[begin + t]);
+            used[t] = 1;
+        }
+    }
+    for (size_t t = 0; t < n; ++t)
+        if (!used[t]) sw.push_back(v[begin + t]);
+    std::copy(sw.begin(), sw.end(), v.begin() + begin);
+}
+
 // Tile order: matrix by matrix, row block by row block, column tiles innermost,
 // so workgroups that run together read neighbouring column strips of the same
 // rows (shared B slice) and the A/B slices of one matrix stay cache-resident
@@ -177,6 +202,7 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
     }
     std::vector<MatDev> hm(c->mats.size());
     std::vector<TileDev> ht;
+    std::vector<int64_t> mat_off(1, 0);
     int64_t elements = 0;
     for (size_t i = 0; i < c->mats.size(); ++i) {
         const adafuse_matrix_desc &m = c->mats[i];
@@ -192,25 +218,18 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
                                      m.out - row0, m.in - col0});
             }
         elements += (int64_t)m.out * m.in;
+        mat_off.push_back((int64_t)ht.size());
     }
-    if (ht.size() > 0x7fffffffu) return ADAFUSE_ERR_SHAPE;
+    if (ht.size() > 0x3fffffffu) return ADAFUSE_ERR_SHAPE;
     if (const char *e = std::getenv("ADAFUSE_ORDER")) c->order = std::atoi(e);
+    // second section: the same tiles grouped per matrix, for the one-launch-per-matrix form
+    const size_t n = ht.size();
+    ht.insert(ht.end(), ht.begin(), ht.begin() + n);
     if (c->order >= 1) {
-        // Workgroup i runs on XCD i % 8.  Hand each XCD runs of G consecutive tiles
-        // (order 1: one run = an eighth of the list) instead of every eighth tile.
-        const size_t n = ht.size();
         const size_t G = c->order == 1 ? (n + 7) / 8 : (size_t)c->order;
-        std::vector<TileDev> sw;
-        sw.reserve(n);
-        std::vector<char> used(n, 0);
-        const size_t slots = ((n + 8 * G - 1) / (8 * G)) * 8 * G;
-        for (size_t i = 0; i < slots; ++i) {
-            const size_t x = i % 8, q = i / 8;
-            const size_t t = ((q / G) * 8 + x) * G + (q % G);
-            if (t < n) { sw.push_back(ht[t]); used[t] = 1; }
-        }
-        for (size_t t = 0; t < n; ++t) if (!used[t]) sw.push_back(ht[t]);
-        ht.swap(sw);
+        deal_to_xcds(ht, 0, n, G);
+        for (size_t i = 0; i + 1 < mat_off.size(); ++i)
+            deal_to_xcds(ht, n + mat_off[i], n + mat_off[i + 1], G);
     }
 
     if (hipGetDevice(&c->device) != hipSuccess) return ADAFUSE_ERR_HIP;
@@ -233,7 +252,8 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
     c->kernel = kernel;
     c->tile_rows = tr;
     c->tile_cols = tc;
-    c->n_tiles = (int64_t)ht.size();
+    c->n_tiles = (int64_t)n;
+    c->mat_tile_off.swap(mat_off);
     c->elements = elements;
     return ADAFUSE_OK;
 }
@@ -320,9 +340,13 @@ adafuse_status adafuse_pregate(const void *hidden, const void *w_router, int32_t
     return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
 }
 
-adafuse_status adafuse_fused_switch(adafuse_ctx *ctx, const int32_t *idx_prev, const float *gates_prev,
-                                    const int32_t *idx_next, const float *gates_next, int32_t k, float scale,
-                                    int32_t mode, void *hip_stream)
+namespace {
+
+// Argument checks shared by the two switch entry points, then one launch per
+// entry of `ranges` (offset, count) into the tile table.
+adafuse_status switch_launches(adafuse_ctx *ctx, const int32_t *idx_prev, const float *gates_prev,
+                               const int32_t *idx_next, const float *gates_next, int32_t k, float scale,
+                               int32_t mode, void *hip_stream, bool per_matrix)
 {
     if (!ctx) return ADAFUSE_ERR_NULL;
     if (mode != ADAFUSE_MERGE && mode != ADAFUSE_UNMERGE && mode != ADAFUSE_SWAP) return ADAFUSE_ERR_ARG;
@@ -334,26 +358,48 @@ adafuse_status adafuse_fused_switch(adafuse_ctx *ctx, const int32_t *idx_prev, c
     if ((need_next || need_prev) && (k < 1 || k > ctx->k_max)) return ADAFUSE_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const bool copy_only = !ctx->inplace && mode == ADAFUSE_UNMERGE;
-    SwitchParams p{ctx->d_mats, ctx->d_tiles, idx_prev, gates_prev, idx_next, gates_next,
-                   copy_only ? 0 : k, ctx->E, ctx->r, mode, scale, ctx->inplace ? 1 : 0};
     const int n_terms = (need_prev ? k : 0) + (need_next ? k : 0);
-    if (ctx->kernel == ADAFUSE_KERNEL_MFMA) {
-        const int64_t n_tiles = ctx->n_tiles;
-        const bool launched = with_shape(ctx->mfma_shape, [&](auto sh) {
-            using S = decltype(sh);
-            if (copy_only) {
-                hipLaunchKernelGGL((switch_copy_kernel<S>), dim3((unsigned)n_tiles), dim3(256), 0, s, p);
-                return true;
-            }
-            return launch_mfma_any<S>(p, terms_bucket(n_terms), n_tiles, s);
-        });
-        if (!launched) return ADAFUSE_ERR_ARG;
-    } else {
-        const size_t lds = valu_lds_bytes(n_terms * ctx->r);
-        if (lds > 64 * 1024) return ADAFUSE_ERR_ARG;  // terms*r beyond what this kernel stages in LDS
-        hipLaunchKernelGGL(switch_valu_kernel, dim3((unsigned)ctx->n_tiles), dim3(256), lds, s, p);
+    const size_t valu_lds = valu_lds_bytes(n_terms * ctx->r);
+    if (ctx->kernel != ADAFUSE_KERNEL_MFMA && valu_lds > 64 * 1024) return ADAFUSE_ERR_ARG;  // terms*r too large to stage
+
+    const size_t n_launches = per_matrix ? ctx->mats.size() : 1;
+    for (size_t i = 0; i < n_launches; ++i) {
+        const int64_t first = per_matrix ? ctx->n_tiles + ctx->mat_tile_off[i] : 0;
+        const int64_t count = per_matrix ? ctx->mat_tile_off[i + 1] - ctx->mat_tile_off[i] : ctx->n_tiles;
+        if (count == 0) continue;
+        SwitchParams p{ctx->d_mats, ctx->d_tiles + first, idx_prev, gates_prev, idx_next, gates_next,
+                       copy_only ? 0 : k, ctx->E, ctx->r, mode, scale, ctx->inplace ? 1 : 0};
+        if (ctx->kernel == ADAFUSE_KERNEL_MFMA) {
+            const bool launched = with_shape(ctx->mfma_shape, [&](auto sh) {
+                using S = decltype(sh);
+                if (copy_only) {
+                    hipLaunchKernelGGL((switch_copy_kernel<S>), dim3((unsigned)count), dim3(256), 0, s, p);
+                    return true;
+                }
+                return launch_mfma_any<S>(p, terms_bucket(n_terms), count, s);
+            });
+            if (!launched) return ADAFUSE_ERR_ARG;
+        } else {
+            hipLaunchKernelGGL(switch_valu_kernel, dim3((unsigned)count), dim3(256), valu_lds, s, p);
+        }
     }
     return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
+}
+
+}  // namespace
+
+adafuse_status adafuse_fused_switch(adafuse_ctx *ctx, const int32_t *idx_prev, const float *gates_prev,
+                                    const int32_t *idx_next, const float *gates_next, int32_t k, float scale,
+                                    int32_t mode, void *hip_stream)
+{
+    return switch_launches(ctx, idx_prev, gates_prev, idx_next, gates_next, k, scale, mode, hip_stream, false);
+}
+
+adafuse_status adafuse_switch_per_matrix(adafuse_ctx *ctx, const int32_t *idx_prev, const float *gates_prev,
+                                         const int32_t *idx_next, const float *gates_next, int32_t k, float scale,
+                                         int32_t mode, void *hip_stream)
+{
+    return switch_launches(ctx, idx_prev, gates_prev, idx_next, gates_next, k, scale, mode, hip_stream, true);
 }
 
 const char *adafuse_status_string(int32_t status)

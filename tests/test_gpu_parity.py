@@ -416,3 +416,43 @@ def test_inplace_full_layer_7b_shape(oracle):
         total += n
     assert diff <= MAX_DIFF_FRACTION * total
     ctx.close()
+
+
+def test_per_matrix_launches_give_the_same_bits(oracle):
+    """The layer-by-layer "simple merge" form is the same update: bit-identical W_work."""
+    wl = wlmod.WORKLOADS["toy"]
+    m = DeviceModel(wl)
+    idx, gates, _ = af.pregate(m.hidden, m.router, wl.k)
+    m.ctx.fused_switch(idx[2], gates[2], idx[3], gates[3], wl.k, wl.scale, af.SWAP)
+    _sync()
+    fused = [ww.clone() for _, ww, _, _ in m.mats]
+    for _, ww, _, _ in m.mats:
+        ww.view(torch.int16).fill_(0x7FC1)
+    m.ctx.switch_per_matrix(idx[2], gates[2], idx[3], gates[3], wl.k, wl.scale, af.SWAP)
+    _sync()
+    for (_, ww, _, _), f in zip(m.mats, fused):
+        assert torch.equal(ww.view(torch.int16), f.view(torch.int16))
+    m.ctx.switch_per_matrix(None, None, None, None, wl.k, wl.scale, af.UNMERGE)
+    _sync()
+    for wb, ww, _, _ in m.mats:
+        assert torch.equal(ww.view(torch.int16), wb.view(torch.int16))
+    m.close()
+    # ragged shapes too, two matrices of different size in one context
+    dev = torch.device("cuda:0")
+    g = torch.Generator().manual_seed(77)
+    mats = []
+    for out, in_ in ((301, 200), (70, 1032)):
+        wb = (0.02 * torch.randn((out, in_), generator=g)).to(torch.bfloat16).to(dev)
+        a = (in_ ** -0.5 * torch.randn((4, 8, in_), generator=g)).to(torch.bfloat16).to(dev)
+        b = (0.05 * torch.randn((4, out, 8), generator=g)).to(torch.bfloat16).to(dev)
+        mats.append((wb, torch.zeros_like(wb), a, b))
+    ctx = af.Context(mats, 2)
+    i2 = torch.tensor([3, 0], dtype=torch.int32, device=dev)
+    g2 = torch.tensor([0.3, 0.7], dtype=torch.float32, device=dev)
+    ctx.switch_per_matrix(None, None, i2, g2, 2, 2.0, af.MERGE)
+    _sync()
+    tally = Tally()
+    for mat in mats:
+        tally.add(check_full(oracle, mat, [3, 0], [0.3, 0.7], 2.0), ULP_TOL)
+    tally.finish(MAX_DIFF_FRACTION)
+    ctx.close()
