@@ -37,7 +37,7 @@ def parse_args():
     ap.add_argument("--per-matrix", action="store_true",
                     help="the paper's 'simple merge' ablation: one launch per adapted matrix instead of one for all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-layers", type=int, default=1, help="layers of the model the oracle is timed on")
+    ap.add_argument("--cpu-layers", type=int, default=2, help="layers of the model the oracle is timed on")
     return ap.parse_args()
 
 
