@@ -53,20 +53,19 @@ def read_traffic(workload, kernel_name):
     return None
 
 
-def cpu_baseline(wl, mats, hidden, router, idx_t, gates_t, n_layers):
-    """Time the oracle (as it stands) on the first n_layers of the model, one switch."""
-    import numpy as np
+def cpu_baseline(wl, mats, hidden, router, t, n_layers):
+    """Time the oracle (as it stands) on the first n_layers of the model: router for token t,
+    then one switch with the oracle's own decision."""
     import adafuse_workloads as wlmod
     import oracle
     per_layer = len(wl.mats)
     sample = mats[: n_layers * per_layer]
     host = [(wlmod.bits(wb), wlmod.bits(a), wlmod.bits(b)) for wb, _, a, b in sample]
-    hb, rb = wlmod.bits(hidden[:1]), wlmod.bits(router)
-    idx = np.asarray(idx_t, np.int32)
-    gates = np.asarray(gates_t, np.float32)
+    hb, rb = wlmod.bits(hidden[t:t + 1]), wlmod.bits(router)
     oracle.lib()
     t0 = time.perf_counter()
-    oracle.pregate(hb, rb, wl.k)
+    dec = oracle.pregate(hb, rb, wl.k)
+    idx, gates = dec["idx"][0], dec["gates32"][0]
     for w, a, b in host:
         oracle.merge(w, a, b, idx, gates, wl.scale)
     dt = time.perf_counter() - t0
@@ -175,8 +174,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         t = (args.warmup + args.steps - 1) % T
-        out["cpu_baseline"] = cpu_baseline(wl, mats, hidden, router, idx[t].cpu().numpy(),
-                                           gates[t].cpu().numpy(), min(args.cpu_layers, wl.layers))
+        out["cpu_baseline"] = cpu_baseline(wl, mats, hidden, router, t, min(args.cpu_layers, wl.layers))
     ctx.close()
     print(json.dumps(out))
 

@@ -31,6 +31,17 @@ class DeviceModel:
         self.ctx.close()
 
 
+def oracle_decisions(oracle, hidden, router, k, device="cuda:0", gate_norm=0):
+    """The ORACLE's routing decisions for a token sequence, on the host and uploaded.
+
+    Switch tests feed these to both sides, so no oracle input ever comes from a HIP kernel.
+    Returns (idx np [T][k], gates32 np [T][k], idx device tensor, gates device tensor).
+    """
+    ref = oracle.pregate(wlmod.bits(hidden), wlmod.bits(router), k, gate_norm)
+    return (ref["idx"], ref["gates32"], torch.from_numpy(ref["idx"]).to(device),
+            torch.from_numpy(ref["gates32"]).to(device))
+
+
 def _line(bits_arr):
     """bf16 bit patterns on the monotone integer line (-0 and +0 coincide)."""
     b = bits_arr.astype(np.int32)
