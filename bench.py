@@ -29,7 +29,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="llama2_7b_all")
-    ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma", "gemm"])
     ap.add_argument("--mode", default="swap", choices=["swap", "unmerge"],
                     help="unmerge times the plain W_base->W_work copy over the same tile table")
     ap.add_argument("--inplace", action="store_true",
@@ -101,9 +101,9 @@ def main():
     hidden = wlmod.gen_hidden(wl, "cuda")
     router = wlmod.gen_router(wl, "cuda")
     ctx = af.Context(mats, wl.k)
-    ctx.set_kernel({"auto": af.KERNEL_AUTO, "valu": af.KERNEL_VALU, "mfma": af.KERNEL_MFMA}[args.kernel])
+    ctx.set_kernel({"auto": af.KERNEL_AUTO, "valu": af.KERNEL_VALU, "mfma": af.KERNEL_MFMA, "gemm": af.KERNEL_GEMM}[args.kernel])
     info = ctx.info()
-    kernel_name = {af.KERNEL_VALU: "valu", af.KERNEL_MFMA: "mfma"}[info.kernel]
+    kernel_name = {af.KERNEL_VALU: "valu", af.KERNEL_MFMA: "mfma", af.KERNEL_GEMM: "gemm"}[info.kernel]
 
     T = wl.T
     idx = torch.empty((T, wl.k), dtype=torch.int32, device=dev)

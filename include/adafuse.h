@@ -60,7 +60,8 @@ typedef enum {
 typedef enum {
     ADAFUSE_KERNEL_AUTO = 0, /* library's choice for the context's (r, k_max) */
     ADAFUSE_KERNEL_VALU = 1, /* rank-(k r) update on the vector ALU, fp32 */
-    ADAFUSE_KERNEL_MFMA = 2  /* per-expert B_e A_e on the matrix cores (bf16 in, fp32 out) */
+    ADAFUSE_KERNEL_MFMA = 2, /* per-expert B_e A_e on the matrix cores (4x4x4 blocks; bf16 in, fp32 out) */
+    ADAFUSE_KERNEL_GEMM = 3  /* high ranks: 32x32x16 matrix-core blocks with a loop over the rank */
 } adafuse_kernel;
 
 /*
@@ -103,8 +104,8 @@ typedef struct {
  * of n_mats descriptors; may be freed afterwards), builds the matrix and tile
  * tables the switch kernel walks and uploads them to the current device.  This
  * is the only call that allocates device memory or synchronises; the tables are
- * a few bytes per tile.  E = experts per bank, r = LoRA rank (4, 8, 16, 32 or
- * 64), k_max = largest k any later call will pass (1 <= k_max <= min(E, 8)).
+ * a few bytes per tile.  E = experts per bank, r = LoRA rank (4, 8, 16, 32, 64
+ * or 128), k_max = largest k any later call will pass (1 <= k_max <= min(E, 8)).
  * In place, k_max <= 4 (a SWAP then carries 2 k_max experts).
  * Errors: NULL mats/ctx or NULL pointer inside a descriptor -> ERR_NULL;
  * n_mats < 1, bad E/r/k_max, reserved != 0, in-place and out-of-place matrices

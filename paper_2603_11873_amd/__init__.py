@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     GATE_SOFTMAX_OVER_TOPK,
     GATE_TOPK_OF_SOFTMAX,
     KERNEL_AUTO,
+    KERNEL_GEMM,
     KERNEL_MFMA,
     KERNEL_VALU,
     MERGE,

@@ -8,7 +8,7 @@ _lib = None
 
 MERGE, UNMERGE, SWAP = 0, 1, 2
 GATE_SOFTMAX_OVER_TOPK, GATE_TOPK_OF_SOFTMAX = 0, 1
-KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA = 0, 1, 2
+KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_GEMM = 0, 1, 2, 3
 
 EXPORTS = ["adafuse_create", "adafuse_destroy", "adafuse_set_kernel", "adafuse_get_info",
            "adafuse_pregate", "adafuse_fused_switch", "adafuse_switch_per_matrix", "adafuse_status_string"]

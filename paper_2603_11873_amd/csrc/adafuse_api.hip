@@ -11,6 +11,7 @@
 
 #include "device_types.hpp"
 #include "pregate.hpp"
+#include "switch_gemm.hpp"
 #include "switch_mfma.hpp"
 #include "switch_valu.hpp"
 
@@ -22,6 +23,7 @@ struct adafuse_ctx {
     int32_t kernel = ADAFUSE_KERNEL_VALU;  // kernel in effect, never AUTO
     int32_t tile_rows = 0, tile_cols = 0;
     int32_t mfma_shape = 0;  // index into the matrix-core kernel's tile shapes
+    int32_t gemm_shape = 0;  // 0: 2 x 2 waves (128 x 128 tile), 1: 1 x 4 waves (64 x 256)
     bool inplace = false;    // every matrix has w_work == w_base
     int32_t order = 128;     // tiles per XCD run (ADAFUSE_ORDER; 0 = plain order, 1 = an eighth of the list)
     int64_t n_tiles = 0, elements = 0;
@@ -51,7 +53,7 @@ adafuse_status validate_mats(const adafuse_matrix_desc *mats, int32_t n_mats, in
     if (!mats) return ADAFUSE_ERR_NULL;
     if (n_mats < 1 || n_mats > 65535) return ADAFUSE_ERR_ARG;
     if (E < 1 || E > kMaxExperts) return ADAFUSE_ERR_ARG;
-    if (r != 4 && r != 8 && r != 16 && r != 32 && r != 64) return ADAFUSE_ERR_ARG;
+    if (r != 4 && r != 8 && r != 16 && r != 32 && r != 64 && r != 128) return ADAFUSE_ERR_ARG;
     if (k_max < 1 || k_max > E || k_max > kMaxTerms) return ADAFUSE_ERR_ARG;
     for (int32_t i = 0; i < n_mats; ++i) {
         const adafuse_matrix_desc &m = mats[i];
@@ -125,6 +127,28 @@ bool launch_mfma_any(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t
     }
 }
 
+template <int R>
+void launch_gemm_r(const SwitchParams &p, int shape, int64_t n_tiles, hipStream_t s)
+{
+    if (shape == 1)
+        hipLaunchKernelGGL((switch_gemm_kernel<R, GemmShape<1, 4>>), dim3((unsigned)n_tiles), dim3(256), 0, s, p);
+    else
+        hipLaunchKernelGGL((switch_gemm_kernel<R, GemmShape<2, 2>>), dim3((unsigned)n_tiles), dim3(256), 0, s, p);
+}
+
+bool launch_gemm(const SwitchParams &p, int shape, int64_t n_tiles, hipStream_t s)
+{
+    switch (p.r) {
+    case 4: launch_gemm_r<4>(p, shape, n_tiles, s); return true;
+    case 8: launch_gemm_r<8>(p, shape, n_tiles, s); return true;
+    case 16: launch_gemm_r<16>(p, shape, n_tiles, s); return true;
+    case 32: launch_gemm_r<32>(p, shape, n_tiles, s); return true;
+    case 64: launch_gemm_r<64>(p, shape, n_tiles, s); return true;
+    case 128: launch_gemm_r<128>(p, shape, n_tiles, s); return true;
+    default: return false;
+    }
+}
+
 // Does the LDS footprint of (r, terms) fit this tile shape?
 bool shape_fits(int shape, int r, int nt)
 {
@@ -149,6 +173,19 @@ int pick_shape(int r, int n_terms)
     for (int sh = 0; sh < kNumShapes; ++sh)
         if (shape_fits(sh, r, nt)) return sh;
     return 0;
+}
+
+// The rank-looped kernel takes any rank that is a multiple of its MFMA depth (16), and 4 or 8 zero-padded to it.
+bool gemm_supported(int r) { return r == 4 || r == 8 || r == 16 || r == 32 || r == 64 || r == 128; }
+
+// Kernel for AUTO, as measured on the Llama-shaped workloads: up to rank 8 the
+// 4x4x4 form (no LDS round trip for W) is a shade faster; from rank 16 on the
+// rank-looped 32x32x16 form wins, by a lot once the inner dimension passes 64.
+int32_t auto_kernel(int r, int n_terms)
+{
+    if (r >= 16 && gemm_supported(r)) return ADAFUSE_KERNEL_GEMM;
+    if (mfma_supported(r, n_terms)) return ADAFUSE_KERNEL_MFMA;
+    return gemm_supported(r) ? ADAFUSE_KERNEL_GEMM : ADAFUSE_KERNEL_VALU;
 }
 
 // Largest term count a launch of this context can carry.
@@ -199,6 +236,11 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
             tc = decltype(sh)::TC;
             return true;
         });
+    } else if (kernel == ADAFUSE_KERNEL_GEMM) {
+        c->gemm_shape = 1;  // 64 x 256: one row of waves, the smaller row-operand stage
+    if (const char *e = std::getenv("ADAFUSE_GEMM_SHAPE")) c->gemm_shape = std::atoi(e) == 1 ? 1 : 0;
+        tr = c->gemm_shape == 1 ? GemmShape<1, 4>::TR : GemmShape<2, 2>::TR;
+        tc = c->gemm_shape == 1 ? GemmShape<1, 4>::TC : GemmShape<2, 2>::TC;
     }
     std::vector<MatDev> hm(c->mats.size());
     std::vector<TileDev> ht;
@@ -280,7 +322,7 @@ adafuse_status adafuse_create(const adafuse_matrix_desc *mats, int32_t n_mats, i
         delete c;
         return ADAFUSE_ERR_ARG;
     }
-    st = build_tables(c, mfma_supported(r, max_terms(c)) ? ADAFUSE_KERNEL_MFMA : ADAFUSE_KERNEL_VALU);
+    st = build_tables(c, auto_kernel(r, max_terms(c)));
     if (st != ADAFUSE_OK) {
         delete c;
         return st;
@@ -300,10 +342,11 @@ adafuse_status adafuse_destroy(adafuse_ctx *ctx)
 adafuse_status adafuse_set_kernel(adafuse_ctx *ctx, int32_t kernel)
 {
     if (!ctx) return ADAFUSE_ERR_NULL;
-    if (kernel == ADAFUSE_KERNEL_AUTO)
-        kernel = mfma_supported(ctx->r, max_terms(ctx)) ? ADAFUSE_KERNEL_MFMA : ADAFUSE_KERNEL_VALU;
-    if (kernel != ADAFUSE_KERNEL_VALU && kernel != ADAFUSE_KERNEL_MFMA) return ADAFUSE_ERR_ARG;
+    if (kernel == ADAFUSE_KERNEL_AUTO) kernel = auto_kernel(ctx->r, max_terms(ctx));
+    if (kernel != ADAFUSE_KERNEL_VALU && kernel != ADAFUSE_KERNEL_MFMA && kernel != ADAFUSE_KERNEL_GEMM)
+        return ADAFUSE_ERR_ARG;
     if (kernel == ADAFUSE_KERNEL_MFMA && !mfma_supported(ctx->r, max_terms(ctx))) return ADAFUSE_ERR_ARG;
+    if (kernel == ADAFUSE_KERNEL_GEMM && !gemm_supported(ctx->r)) return ADAFUSE_ERR_ARG;
     if (kernel == ctx->kernel) return ADAFUSE_OK;
     if (hipDeviceSynchronize() != hipSuccess) return ADAFUSE_ERR_HIP;  // no launch may still read the old table
     return build_tables(ctx, kernel);
@@ -360,7 +403,7 @@ adafuse_status switch_launches(adafuse_ctx *ctx, const int32_t *idx_prev, const 
     const bool copy_only = !ctx->inplace && mode == ADAFUSE_UNMERGE;
     const int n_terms = (need_prev ? k : 0) + (need_next ? k : 0);
     const size_t valu_lds = valu_lds_bytes(n_terms * ctx->r);
-    if (ctx->kernel != ADAFUSE_KERNEL_MFMA && valu_lds > 64 * 1024) return ADAFUSE_ERR_ARG;  // terms*r too large to stage
+    if (ctx->kernel == ADAFUSE_KERNEL_VALU && valu_lds > 64 * 1024) return ADAFUSE_ERR_ARG;  // terms*r too large to stage
 
     const size_t n_launches = per_matrix ? ctx->mats.size() : 1;
     for (size_t i = 0; i < n_launches; ++i) {
@@ -379,6 +422,8 @@ adafuse_status switch_launches(adafuse_ctx *ctx, const int32_t *idx_prev, const 
                 return launch_mfma_any<S>(p, terms_bucket(n_terms), count, s);
             });
             if (!launched) return ADAFUSE_ERR_ARG;
+        } else if (ctx->kernel == ADAFUSE_KERNEL_GEMM) {
+            if (!launch_gemm(p, ctx->gemm_shape, count, s)) return ADAFUSE_ERR_ARG;
         } else {
             hipLaunchKernelGGL(switch_valu_kernel, dim3((unsigned)count), dim3(256), valu_lds, s, p);
         }

@@ -1,0 +1,283 @@
+// Fused switch for high LoRA ranks (the paper's "typical" r = 64 or 128 with
+// top-2: inner dimension 128..256, twice that in place).  Here the low-rank
+// product is a real contraction, so it runs on the wide matrix-core shape
+// v_mfma_f32_32x32x16_bf16 with a loop over the rank, one expert after another.
+//
+// A wave owns a 64 x 64 piece of W (2 x 2 MFMA blocks, 64 fp32 accumulators per
+// lane); the 4 waves of a workgroup share one barrier per expert.
+//   * W: the wave's 8 KB are requested first (8 x 128-bit per lane) and consumed
+//     last, so the whole contraction runs under that latency.
+//   * Column operand (A bank, [rank][in]): block cb of a wave takes the even
+//     (cb=0) / odd (cb=1) columns of its 64, so the operands of both blocks for
+//     one rank index are the two halves of ONE aligned 32-bit word: 8 coalesced
+//     dword loads per 16 rank indices, packed with byte permutes.
+//   * Row operand (B bank, [out][rank]): one expert's rows of the tile are one
+//     contiguous piece of memory; the workgroup fetches it coalesced into LDS
+//     (double buffered: the next expert's while this one's MFMAs run), and a lane
+//     reads its 8 rank indices of a row as one 16-byte LDS read.
+//   * Result layout with that column assignment: a lane holds, per row block and
+//     b = 0..3, the 8 contiguous columns base + 16 b + 8 (lane/32) + 0..7 of row
+//     lane%32 -- one 128-bit access of W each.
+// Gates stay out of the bf16 operands.  Experts are chained in ONE accumulator:
+//   acc = P_0;  acc = acc * (c_0/c_1) + P_1;  ...;  W' = rn_bf16(W + c_last * acc)
+// which equals W + sum_j c_j P_j up to fp32 rounding of the ratios (terms with a
+// zero coefficient are skipped, so no ratio divides by zero).
+#pragma once
+#include "device_types.hpp"
+
+namespace adafuse {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float float16_t;
+
+constexpr int kGemmWaveRows = 64;
+constexpr int kGemmWaveCols = 64;
+
+// WRW x WCW waves per workgroup (4 waves); tile = (64 WRW) x (64 WCW)
+template <int WRW_, int WCW_>
+struct GemmShape {
+    static constexpr int WRW = WRW_, WCW = WCW_;
+    static constexpr int TR = kGemmWaveRows * WRW_;
+    static constexpr int TC = kGemmWaveCols * WCW_;
+    static_assert(WRW_ * WCW_ == 4, "4 waves per workgroup");
+};
+
+template <int R, class S>
+__global__ __launch_bounds__(256) void switch_gemm_kernel(SwitchParams p)
+{
+    static_assert(R % 16 == 0 || R == 8 || R == 4, "rank must be a multiple of the MFMA depth, or 4 or 8 (zero padded)");
+    constexpr int KS = (R + 15) / 16;   // k-steps per expert
+    constexpr bool kPadded = R < 16;    // one k-step whose rank indices >= R are zero
+    constexpr int TR = S::TR;           // tile rows
+    constexpr int RP = R < 8 ? 8 : R;   // rank padded to one 16-byte piece
+    constexpr int BP = (R < 16 ? 16 : R) + 8;  // LDS row pitch of the staged B slice (bf16): 16-byte pad against bank conflicts
+    constexpr int BV = TR * RP / 8;     // 16-byte pieces of one expert's B slice for the tile
+    constexpr int BQ = (BV + 255) / 256;  // ... per thread
+    constexpr int TC = S::TC;           // tile columns
+    constexpr int WP = TC + 8;          // LDS row pitch of the W tile (bf16)
+    constexpr int WQ = TR * TC / 8 / 256;  // 16-byte pieces of the W tile per thread
+
+    __shared__ int32_t s_e[kMaxTerms];
+    __shared__ float s_c[kMaxTerms];
+    __shared__ __align__(16) uint16_t s_b[2][TR][BP];  // row operand of the current / next expert
+    __shared__ __align__(16) uint16_t s_w[TR][WP];     // the W tile, on its way in and out
+    {
+        Terms terms;
+        if (!load_terms<kMaxTerms>(p, terms)) return;
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int j = 0; j < kMaxTerms; ++j) {
+                s_e[j] = terms.e[j];
+                s_c[j] = terms.c[j];
+            }
+        }
+    }
+
+    const TileDev tile = p.tiles[blockIdx.x];
+    const MatDev m = p.mats[tile.mat];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wr = wave / S::WCW, wc = wave % S::WCW;
+    const int n = lane & 31;   // row inside a 32-row block (MFMA N index)
+    const int h = lane >> 5;   // which half of the k-step / of a 16-column group
+
+    const int lrow0 = kGemmWaveRows * wr;              // wave origin inside the tile
+    const int lcol0 = kGemmWaveCols * wc;
+    const int rows_left = tile.rows_left, cols_left = tile.cols_left;
+    const int ldw = tile.ldw;
+
+    // ---- W first.  The 32x32 result layout gives a lane 16-byte pieces of 32
+    // different rows, which streams badly; so the workgroup moves its W tile with
+    // row-contiguous accesses (a wave instruction = whole 512-byte row pieces) and
+    // turns it into the result layout through LDS, both ways.  Out-of-range pieces
+    // read a clamped (valid) address -- unconditional loads schedule freely -- and
+    // are never stored.
+    uint4_t wreg[WQ];
+#pragma unroll
+    for (int i = 0; i < WQ; ++i) {
+        const int q = tid + 256 * i;
+        const int row = q / (TC / 8), pc = q % (TC / 8);
+        const int cr = row < rows_left ? row : rows_left - 1;
+        const int cc = 8 * pc < cols_left ? 8 * pc : cols_left - 8;
+        wreg[i] = ld_global_nt(reinterpret_cast<const uint4_t *>(tile.w_src + (size_t)cr * ldw + cc));
+    }
+    __syncthreads();  // term list visible
+
+    float16_t acc[2][2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.0f;
+
+    // Column operand addressing, clamped the same way: a column beyond the edge
+    // only feeds result columns that are never stored.
+    int acol = lcol0 + 2 * n;                                  // this lane's column pair, inside the tile
+    acol = tile.col0 + (acol < cols_left ? acol : cols_left - 2);
+
+    // The row operand of one expert for the whole tile -- TR rows x R, contiguous in
+    // the B bank -- is fetched by the workgroup in 16-byte pieces (fully coalesced)
+    // and kept in LDS; rows beyond the edge repeat the last row.
+    auto fetch_b = [&](uint4_t (&v)[BQ], int e) {
+        const uint16_t *bsrc = m.b_bank + ((size_t)e * m.out + tile.row0) * R;
+#pragma unroll
+        for (int i = 0; i < BQ; ++i) {
+            const int q = tid + 256 * i;
+            const int row = q / (RP / 8), piece = q % (RP / 8);
+            const int cr = row < rows_left ? row : rows_left - 1;
+            if (q < BV) {
+                if constexpr (R >= 8) {
+                    v[i] = ld_global(reinterpret_cast<const uint4_t *>(bsrc + (size_t)cr * R + 8 * piece));
+                } else {  // rank 4: a row is 8 bytes
+                    const uint2_t t = ld_global(reinterpret_cast<const uint2_t *>(bsrc + (size_t)cr * R));
+                    v[i] = uint4_t{t[0], t[1], 0u, 0u};
+                }
+            }
+        }
+    };
+    auto stash_b = [&](const uint4_t (&v)[BQ], int buf) {
+#pragma unroll
+        for (int i = 0; i < BQ; ++i) {
+            const int q = tid + 256 * i;
+            const int row = q / (RP / 8), piece = q % (RP / 8);
+            if (q < BV) {
+                *reinterpret_cast<uint4_t *>(&s_b[buf][row][8 * piece]) = v[i];
+                if constexpr (kPadded)  // second half of the single k-step: zeros
+                    *reinterpret_cast<uint4_t *>(&s_b[buf][row][8]) = uint4_t{0u, 0u, 0u, 0u};
+            }
+        }
+    };
+    // Column operands are fetched a chunk (KCH k-steps = 16 KCH rank indices) ahead.
+    constexpr int KCH = KS >= 8 ? 2 : (KS >= 4 ? 4 : KS);
+    constexpr int NCH = KS / KCH;
+    struct XChunk {
+        uint32_t d[KCH][8];
+    };
+    auto fetch_x = [&](XChunk &x, int e, int kc) {
+        if constexpr (kPadded) {
+            // rank indices 8h + i beyond R are zero: read a clamped index, then clear
+            const uint16_t *abase = m.a_bank + (size_t)e * R * m.in + acol;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int kap = 8 * h + i;
+                const uint32_t v = ld_global(reinterpret_cast<const uint32_t *>(abase + (size_t)(kap < R ? kap : R - 1) * m.in));
+                x.d[0][i] = kap < R ? v : 0u;
+            }
+        } else {
+            const uint16_t *abase = m.a_bank + ((size_t)e * R + 16 * KCH * kc + 8 * h) * m.in + acol;
+#pragma unroll
+            for (int s2 = 0; s2 < KCH; ++s2)
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    x.d[s2][i] = ld_global(reinterpret_cast<const uint32_t *>(abase + (size_t)(16 * s2 + i) * m.in));
+        }
+    };
+    auto term_coeff = [&](int j) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(s_c[j]))); };
+    auto term_expert = [&](int j) { return __builtin_amdgcn_readfirstlane(s_e[j]); };
+    // every lane reads the same term list, so this is scalar control flow
+    auto next_term = [&](int j, int nt_) {
+        while (j < nt_ && term_coeff(j) == 0.0f) ++j;  // a zero coefficient contributes nothing: skipped
+        return j;
+    };
+
+    const int nt = p.inplace ? (p.mode == 2 ? 2 * p.k : p.k) : p.k;
+    float c_last = 0.0f;
+    int j = next_term(0, nt);
+    int buf = 0;
+    uint4_t vb[BQ];
+    XChunk xcur, xnxt;
+    if (j < nt) {
+        fetch_b(vb, term_expert(j));
+        fetch_x(xcur, term_expert(j), 0);
+    }
+    // W tile into LDS now (its loads were issued first, so they are the first to land):
+    // the registers are free for the contraction
+#pragma unroll
+    for (int i = 0; i < WQ; ++i) {
+        const int q = tid + 256 * i;
+        *reinterpret_cast<uint4_t *>(&s_w[q / (TC / 8)][8 * (q % (TC / 8))]) = wreg[i];
+    }
+    if (j < nt) stash_b(vb, 0);
+    __syncthreads();
+    while (j < nt) {
+        const float c = term_coeff(j);
+        const int e = term_expert(j);
+        const int jn = next_term(j + 1, nt);
+        if (jn < nt) fetch_b(vb, term_expert(jn));  // next expert's row operand: in flight during this expert's MFMAs
+        if (c_last != 0.0f) {
+            const float ratio = c_last / c;
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[rb][cb][v] *= ratio;
+        }
+        c_last = c;
+#pragma unroll 1
+        for (int kc = 0; kc < NCH; ++kc) {
+            if (kc + 1 < NCH)
+                fetch_x(xnxt, e, kc + 1);
+            else if (jn < nt)
+                fetch_x(xnxt, term_expert(jn), 0);
+#pragma unroll
+            for (int s2 = 0; s2 < KCH; ++s2) {
+                const uint32_t *d = xcur.d[s2];
+                const int ks = kc * KCH + s2;
+                uint4_t y[2];
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb)
+                    y[rb] = *reinterpret_cast<const uint4_t *>(&s_b[buf][lrow0 + 32 * rb + n][16 * ks + 8 * h]);
+                const uint4_t xe = {__builtin_amdgcn_perm(d[1], d[0], 0x05040100u), __builtin_amdgcn_perm(d[3], d[2], 0x05040100u),
+                                    __builtin_amdgcn_perm(d[5], d[4], 0x05040100u), __builtin_amdgcn_perm(d[7], d[6], 0x05040100u)};
+                const uint4_t xo = {__builtin_amdgcn_perm(d[1], d[0], 0x07060302u), __builtin_amdgcn_perm(d[3], d[2], 0x07060302u),
+                                    __builtin_amdgcn_perm(d[5], d[4], 0x07060302u), __builtin_amdgcn_perm(d[7], d[6], 0x07060302u)};
+                const bf16x8_t x0 = __builtin_bit_cast(bf16x8_t, xe), x1 = __builtin_bit_cast(bf16x8_t, xo);
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) {
+                    const bf16x8_t yy = __builtin_bit_cast(bf16x8_t, y[rb]);
+                    acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0, yy, acc[rb][0], 0, 0, 0);
+                    acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1, yy, acc[rb][1], 0, 0, 0);
+                }
+            }
+            xcur = xnxt;
+        }
+        if (jn < nt) stash_b(vb, buf ^ 1);
+        __syncthreads();  // next buffer complete, and everyone is done reading this one before it is reused
+        buf ^= 1;
+        j = jn;
+    }
+
+    // ---- epilogue: each lane updates its pieces of the W tile in LDS, in the result
+    // layout (column p of a group is accumulator cb = p&1, v = 4b + p/2); tile back out.
+    if (nt > 0) {  // nothing selected (un-merge out of place): the bits pass through untouched
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                uint4_t *slot = reinterpret_cast<uint4_t *>(&s_w[lrow0 + 32 * rb + n][lcol0 + 16 * b + 8 * h]);
+                const uint4_t wv = *slot;
+                float o[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) o[q] = c_last * acc[rb][q & 1][4 * b + (q >> 1)];
+                uint4_t out;
+#pragma unroll
+                for (int hh = 0; hh < 4; ++hh)
+                    out[hh] = pack_bf16_rne(o[2 * hh] + bf16_lo(wv[hh]), o[2 * hh + 1] + bf16_hi(wv[hh]));
+                *slot = out;
+            }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < WQ; ++i) {
+        const int q = tid + 256 * i;
+        const int row = q / (TC / 8), pc = q % (TC / 8);
+        if (row < rows_left && 8 * pc < cols_left)
+            st_global_nt(*reinterpret_cast<const uint4_t *>(&s_w[row][8 * pc]),
+                         reinterpret_cast<uint4_t *>(tile.w_dst + (size_t)row * ldw + 8 * pc));
+    }
+}
+
+}  // namespace adafuse

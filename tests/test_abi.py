@@ -55,7 +55,7 @@ def test_create_rejects_bad_arguments(L):
     assert _create(L, [_desc()], E=0)[0] == ERR_ARG
     assert _create(L, [_desc()], E=65)[0] == ERR_ARG
     assert _create(L, [_desc()], r=7)[0] == ERR_ARG
-    assert _create(L, [_desc()], r=128)[0] == ERR_ARG
+    assert _create(L, [_desc()], r=256)[0] == ERR_ARG
     assert _create(L, [_desc()], k_max=0)[0] == ERR_ARG
     assert _create(L, [_desc()], E=4, k_max=5)[0] == ERR_ARG
     assert _create(L, [_desc()], E=16, k_max=9)[0] == ERR_ARG

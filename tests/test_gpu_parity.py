@@ -20,6 +20,7 @@ GATE_RTOL = 1e-5
 MAX_DIFF_FRACTION = 0.01   # elements allowed to differ at all (near-ties of the rounding)
 
 KERNELS = [af.KERNEL_VALU, af.KERNEL_MFMA]
+ALL_KERNELS = KERNELS + [af.KERNEL_GEMM]
 
 
 def _sync():
@@ -79,7 +80,7 @@ def test_pregate_exact_tie_and_single_token(oracle):
     assert order.index(1) + 1 == order.index(3) and order.index(3) + 1 == order.index(4)
 
 
-@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("kernel", ALL_KERNELS)
 def test_toy_every_token_every_element_all_modes(oracle, kernel):
     wl = wlmod.WORKLOADS["toy"]
     m = DeviceModel(wl)
@@ -103,7 +104,7 @@ def test_toy_every_token_every_element_all_modes(oracle, kernel):
     m.close()
 
 
-@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("kernel", ALL_KERNELS)
 def test_invariants_on_device(oracle, kernel):
     wl = wlmod.WORKLOADS["toy"]
     m = DeviceModel(wl)
@@ -180,10 +181,14 @@ RAGGED = [  # (out, in, ldw, E, r, k)
     (70, 264, 272, 4, 32, 2),
     (66, 120, 120, 2, 64, 1),
     (513, 520, 520, 16, 8, 8),
+    (200, 328, 328, 4, 64, 2),
+    (129, 136, 144, 2, 128, 2),
+    (64, 64, 64, 4, 128, 1),
+    (331, 72, 72, 8, 32, 4),
 ]
 
 
-@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("kernel", ALL_KERNELS)
 @pytest.mark.parametrize("out,in_,ldw,E,r,k", RAGGED)
 def test_ragged_shapes_and_padding(oracle, kernel, out, in_, ldw, E, r, k):
     dev = torch.device("cuda:0")
@@ -198,10 +203,15 @@ def test_ragged_shapes_and_padding(oracle, kernel, out, in_, ldw, E, r, k):
     try:
         ctx.set_kernel(kernel)
     except af.AdafuseError:
-        assert kernel == af.KERNEL_MFMA
-        pytest.skip("matrix-core kernel is not instantiated for this (r, k)")
+        assert kernel != af.KERNEL_VALU
+        pytest.skip("this kernel is not built for this (r, k)")
     idx = torch.randperm(E, generator=g)[:k].to(torch.int32).to(dev)
     gates = torch.softmax(torch.randn(k, generator=g), 0).to(dev)
+    if kernel == af.KERNEL_VALU and k * r * 768 > 65536:
+        with pytest.raises(af.AdafuseError):       # more than this kernel can stage in LDS: refused, not launched
+            ctx.fused_switch(None, None, idx, gates, k, 2.0, af.MERGE)
+        ctx.close()
+        return
     ctx.fused_switch(None, None, idx, gates, k, 2.0, af.MERGE)
     _sync()
     tally = Tally()
@@ -216,7 +226,7 @@ def test_ragged_shapes_and_padding(oracle, kernel, out, in_, ldw, E, r, k):
     ctx.close()
 
 
-@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("kernel", ALL_KERNELS)
 def test_one_full_layer_of_the_7b_shape(oracle, kernel):
     """Every element of the seven matrices of one Llama-2-7B-shaped layer (several
     hundred tiles per matrix, 11008 is not a multiple of the tile height)."""
@@ -317,7 +327,7 @@ def _check_inplace_step(oracle, before, mat, prev, nxt, scale):
     return nd, want.size
 
 
-@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("kernel", ALL_KERNELS)
 def test_inplace_steps_match_oracle(oracle, kernel):
     """Every token transition of the toy sequence as ONE in-place step.  The state before the
     step is built by the oracle (W_base merged with the previous token's experts), uploaded,
@@ -480,5 +490,60 @@ def test_per_matrix_launches_give_the_same_bits(oracle):
     tally = Tally()
     for mat in mats:
         tally.add(check_full(oracle, mat, [3, 0], [0.3, 0.7], 2.0), ULP_TOL)
+    tally.finish(MAX_DIFF_FRACTION)
+    ctx.close()
+
+
+@pytest.mark.parametrize("r,k,inplace", [(64, 2, False), (128, 2, False), (64, 2, True), (16, 4, False), (32, 1, True)])
+def test_rank_looped_kernel_modes(oracle, r, k, inplace):
+    """The high-rank kernel: MERGE / SWAP / UNMERGE, out of place and in place, two ragged matrices."""
+    dev = torch.device("cuda:0")
+    g = torch.Generator().manual_seed(r * 10 + k)
+    E = 4
+    mats, base = [], []
+    for out, in_ in ((190, 264), (64, 128)):
+        wb = (0.02 * torch.randn((out, in_), generator=g)).to(torch.bfloat16).to(dev)
+        a = (in_ ** -0.5 * torch.randn((E, r, in_), generator=g)).to(torch.bfloat16).to(dev)
+        b = (0.02 * torch.randn((E, out, r), generator=g)).to(torch.bfloat16).to(dev)
+        base.append(wb.clone())
+        mats.append((wb, wb if inplace else torch.zeros_like(wb), a, b))
+    ctx = af.Context(mats, k)
+    ctx.set_kernel(af.KERNEL_GEMM)
+    assert ctx.info().kernel == af.KERNEL_GEMM
+    sel = []
+    for _ in range(2):
+        idx = torch.randperm(E, generator=g)[:k].to(torch.int32)
+        gates = torch.softmax(torch.randn(k, generator=g), 0)
+        sel.append((idx.numpy(), gates.numpy(), idx.to(dev), gates.to(dev)))
+    (i0, g0, di0, dg0), (i1, g1, di1, dg1) = sel
+    host = [(wlmod.bits(wb), wlmod.bits(m[2]), wlmod.bits(m[3])) for wb, m in zip(base, mats)]
+    ctx.fused_switch(None, None, di0, dg0, k, 2.0, af.MERGE)
+    _sync()
+    tally = Tally()
+    for (w, a, b), m in zip(host, mats):
+        tally.add(compare(oracle, w, a, b, wlmod.bits(m[1]), i0, g0, 2.0), ULP_TOL)
+    if inplace:
+        # one Eq.8 step from an oracle-built state
+        before = [oracle.merge(w, a, b, i0, g0, 2.0) for w, a, b in host]
+        for m, bf in zip(mats, before):
+            m[1].copy_(wlmod.from_bits(bf))
+        ctx.fused_switch(di0, dg0, di1, dg1, k, 2.0, af.SWAP)
+        _sync()
+        for m, bf in zip(mats, before):
+            _check_inplace_step(oracle, bf, m, (i0, g0), (i1, g1), 2.0)
+    else:
+        ctx.fused_switch(di0, dg0, di1, dg1, k, 2.0, af.SWAP)
+        _sync()
+        for (w, a, b), m in zip(host, mats):
+            tally.add(compare(oracle, w, a, b, wlmod.bits(m[1]), i1, g1, 2.0), ULP_TOL)
+        ctx.fused_switch(None, None, None, None, k, 2.0, af.UNMERGE)
+        _sync()
+        for wb, m in zip(base, mats):
+            assert torch.equal(m[1].view(torch.int16), wb.view(torch.int16))
+        # zero gates: bit-identical
+        ctx.fused_switch(None, None, di0, torch.zeros_like(dg0), k, 2.0, af.MERGE)
+        _sync()
+        for wb, m in zip(base, mats):
+            assert torch.equal(m[1].view(torch.int16), wb.view(torch.int16))
     tally.finish(MAX_DIFF_FRACTION)
     ctx.close()
