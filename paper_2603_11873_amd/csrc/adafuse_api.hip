@@ -23,7 +23,6 @@ struct adafuse_ctx {
     int32_t kernel = ADAFUSE_KERNEL_VALU;  // kernel in effect, never AUTO
     int32_t tile_rows = 0, tile_cols = 0;
     int32_t mfma_shape = 0;  // index into the matrix-core kernel's tile shapes
-    int32_t gemm_shape = 0;  // 0: 2 x 2 waves (128 x 128 tile), 1: 1 x 4 waves (64 x 256)
     bool inplace = false;    // every matrix has w_work == w_base
     int32_t order = 128;     // tiles per XCD run (ADAFUSE_ORDER; 0 = plain order, 1 = an eighth of the list)
     int64_t n_tiles = 0, elements = 0;
@@ -128,23 +127,27 @@ bool launch_mfma_any(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t
 }
 
 template <int R>
-void launch_gemm_r(const SwitchParams &p, int shape, int64_t n_tiles, hipStream_t s)
+bool launch_gemm_r(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t s)
 {
-    if (shape == 1)
-        hipLaunchKernelGGL((switch_gemm_kernel<R, GemmShape<1, 4>>), dim3((unsigned)n_tiles), dim3(256), 0, s, p);
-    else
-        hipLaunchKernelGGL((switch_gemm_kernel<R, GemmShape<2, 2>>), dim3((unsigned)n_tiles), dim3(256), 0, s, p);
+    switch (nt) {
+    case 1: hipLaunchKernelGGL((switch_gemm_kernel<R, 1>), dim3((unsigned)n_tiles), dim3(256), 0, s, p); return true;
+    case 2: hipLaunchKernelGGL((switch_gemm_kernel<R, 2>), dim3((unsigned)n_tiles), dim3(256), 0, s, p); return true;
+    case 4:
+    case 8: hipLaunchKernelGGL((switch_gemm_loop_kernel<R>), dim3((unsigned)n_tiles), dim3(256), 0, s, p); return true;
+    default: return false;
+    }
 }
 
-bool launch_gemm(const SwitchParams &p, int shape, int64_t n_tiles, hipStream_t s)
+// nt = term bucket (1, 2, 4 or 8)
+bool launch_gemm(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t s)
 {
     switch (p.r) {
-    case 4: launch_gemm_r<4>(p, shape, n_tiles, s); return true;
-    case 8: launch_gemm_r<8>(p, shape, n_tiles, s); return true;
-    case 16: launch_gemm_r<16>(p, shape, n_tiles, s); return true;
-    case 32: launch_gemm_r<32>(p, shape, n_tiles, s); return true;
-    case 64: launch_gemm_r<64>(p, shape, n_tiles, s); return true;
-    case 128: launch_gemm_r<128>(p, shape, n_tiles, s); return true;
+    case 4: return launch_gemm_r<4>(p, nt, n_tiles, s);
+    case 8: return launch_gemm_r<8>(p, nt, n_tiles, s);
+    case 16: return launch_gemm_r<16>(p, nt, n_tiles, s);
+    case 32: return launch_gemm_r<32>(p, nt, n_tiles, s);
+    case 64: return launch_gemm_r<64>(p, nt, n_tiles, s);
+    case 128: return launch_gemm_r<128>(p, nt, n_tiles, s);
     default: return false;
     }
 }
@@ -178,14 +181,14 @@ int pick_shape(int r, int n_terms)
 // The rank-looped kernel takes any rank that is a multiple of its MFMA depth (16), and 4 or 8 zero-padded to it.
 bool gemm_supported(int r) { return r == 4 || r == 8 || r == 16 || r == 32 || r == 64 || r == 128; }
 
-// Kernel for AUTO, as measured on the Llama-shaped workloads: up to rank 8 the
-// 4x4x4 form (no LDS round trip for W) is a shade faster; from rank 16 on the
-// rank-looped 32x32x16 form wins, by a lot once the inner dimension passes 64.
+// Kernel for AUTO, as measured on the Llama-shaped workloads: the rank-looped
+// 32x32x16 form is the fastest at every rank (80% of the HBM peak against 79% for
+// the 4x4x4 form at rank 8, and far ahead once the inner dimension passes 64).
 int32_t auto_kernel(int r, int n_terms)
 {
-    if (r >= 16 && gemm_supported(r)) return ADAFUSE_KERNEL_GEMM;
+    if (gemm_supported(r)) return ADAFUSE_KERNEL_GEMM;
     if (mfma_supported(r, n_terms)) return ADAFUSE_KERNEL_MFMA;
-    return gemm_supported(r) ? ADAFUSE_KERNEL_GEMM : ADAFUSE_KERNEL_VALU;
+    return ADAFUSE_KERNEL_VALU;
 }
 
 // Largest term count a launch of this context can carry.
@@ -237,10 +240,8 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
             return true;
         });
     } else if (kernel == ADAFUSE_KERNEL_GEMM) {
-        c->gemm_shape = 1;  // 64 x 256: one row of waves, the smaller row-operand stage
-    if (const char *e = std::getenv("ADAFUSE_GEMM_SHAPE")) c->gemm_shape = std::atoi(e) == 1 ? 1 : 0;
-        tr = c->gemm_shape == 1 ? GemmShape<1, 4>::TR : GemmShape<2, 2>::TR;
-        tc = c->gemm_shape == 1 ? GemmShape<1, 4>::TC : GemmShape<2, 2>::TC;
+        tr = kGemmTileRows;
+        tc = kGemmTileCols;
     }
     std::vector<MatDev> hm(c->mats.size());
     std::vector<TileDev> ht;
@@ -423,7 +424,8 @@ adafuse_status switch_launches(adafuse_ctx *ctx, const int32_t *idx_prev, const 
             });
             if (!launched) return ADAFUSE_ERR_ARG;
         } else if (ctx->kernel == ADAFUSE_KERNEL_GEMM) {
-            if (!launch_gemm(p, ctx->gemm_shape, count, s)) return ADAFUSE_ERR_ARG;
+            // the copy (nothing selected) runs through the one-term instance
+            if (!launch_gemm(p, terms_bucket(n_terms > 0 ? n_terms : 1), count, s)) return ADAFUSE_ERR_ARG;
         } else {
             hipLaunchKernelGGL(switch_valu_kernel, dim3((unsigned)count), dim3(256), valu_lds, s, p);
         }

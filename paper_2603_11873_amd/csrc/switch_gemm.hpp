@@ -1,23 +1,37 @@
-// Fused switch for high LoRA ranks (the paper's "typical" r = 64 or 128 with
-// top-2: inner dimension 128..256, twice that in place).  Here the low-rank
-// product is a real contraction, so it runs on the wide matrix-core shape
-// v_mfma_f32_32x32x16_bf16 with a loop over the rank, one expert after another.
+// Fused switch, rank-looped form: the default from rank 16 on, and the only form
+// for the paper's "typical" ranks 64 and 128 (inner dimension 128..256 with
+// top-2, twice that in place).  Here the low-rank product is a real contraction,
+// so it runs on the wide matrix-core shape v_mfma_f32_32x32x16_bf16, one expert
+// after another.
 //
 // A wave owns a 64 x 64 piece of W (2 x 2 MFMA blocks, 64 fp32 accumulators per
-// lane); the 4 waves of a workgroup share one barrier per expert.
-//   * W: the wave's 8 KB are requested first (8 x 128-bit per lane) and consumed
-//     last, so the whole contraction runs under that latency.
+// lane); a workgroup is 4 waves side by side on a 64 x 256 tile.
+//   * W through LDS.  The 32x32 result layout gives a lane 16-byte pieces of 32
+//     different rows, which streams badly (every access touches 32 cache lines
+//     for 1 KB).  So the workgroup moves its W tile with row-contiguous 128-bit
+//     accesses (a wave instruction = two whole 512-byte row pieces), parks it in
+//     LDS as soon as it lands, each lane updates its pieces there in the result
+//     layout, and the tile goes back out the same way.
+//   * Row operand (B bank, [out][rank]): one expert's rows of the tile are one
+//     contiguous piece of memory; the workgroup fetches it coalesced into LDS,
+//     as many experts up front as the LDS budget holds (all of them in the usual
+//     cases, so the main loop has no barrier), the rest rolling.  A lane reads
+//     its 8 rank indices of a row as one 16-byte LDS read.
 //   * Column operand (A bank, [rank][in]): block cb of a wave takes the even
 //     (cb=0) / odd (cb=1) columns of its 64, so the operands of both blocks for
 //     one rank index are the two halves of ONE aligned 32-bit word: 8 coalesced
-//     dword loads per 16 rank indices, packed with byte permutes.
-//   * Row operand (B bank, [out][rank]): one expert's rows of the tile are one
-//     contiguous piece of memory; the workgroup fetches it coalesced into LDS
-//     (double buffered: the next expert's while this one's MFMAs run), and a lane
-//     reads its 8 rank indices of a row as one 16-byte LDS read.
+//     dword loads per 16 rank indices, packed with byte permutes, kept in a
+//     register queue that runs several chunks ahead of the MFMAs.
 //   * Result layout with that column assignment: a lane holds, per row block and
 //     b = 0..3, the 8 contiguous columns base + 16 b + 8 (lane/32) + 0..7 of row
-//     lane%32 -- one 128-bit access of W each.
+//     lane%32 -- one 16-byte piece of the W tile each.
+// Everything the tile needs is requested at the start, in the order it is used
+// (loads return in issue order): W, row operands, the first column operands.
+// All loads are unconditional with clamped addresses: a row or column beyond the
+// matrix edge only feeds results that are never stored, and loads inside
+// branches would each get their own wait.
+// Two forms: switch_gemm_kernel<R, NT> for 1 or 2 terms (the usual top-2, out of
+// place), fully unrolled; switch_gemm_loop_kernel<R> for more.
 // Gates stay out of the bf16 operands.  Experts are chained in ONE accumulator:
 //   acc = P_0;  acc = acc * (c_0/c_1) + P_1;  ...;  W' = rn_bf16(W + c_last * acc)
 // which equals W + sum_j c_j P_j up to fp32 rounding of the ratios (terms with a
@@ -30,30 +44,262 @@ namespace adafuse {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float float16_t;
 
-constexpr int kGemmWaveRows = 64;
-constexpr int kGemmWaveCols = 64;
+constexpr int kGemmTileRows = 64;
+constexpr int kGemmTileCols = 256;
 
-// WRW x WCW waves per workgroup (4 waves); tile = (64 WRW) x (64 WCW)
-template <int WRW_, int WCW_>
-struct GemmShape {
-    static constexpr int WRW = WRW_, WCW = WCW_;
-    static constexpr int TR = kGemmWaveRows * WRW_;
-    static constexpr int TC = kGemmWaveCols * WCW_;
-    static_assert(WRW_ * WCW_ == 4, "4 waves per workgroup");
+template <int R, int NT>
+struct GemmPlan {
+    static constexpr int KS = (R + 15) / 16;          // k-steps (16 rank indices) per expert
+    static constexpr bool kPadded = R < 16;           // one k-step whose rank indices >= R are zero
+    static constexpr int KCH = KS >= 2 ? 2 : 1;       // k-steps per column-operand chunk
+    static constexpr int NCH = KS / KCH;              // chunks per expert
+    static constexpr int TOT = NT * NCH;              // chunks per tile
+    static constexpr int QMAX = KCH == 1 ? 8 : 4;     // chunks in flight: at most 64 VGPRs
+    static constexpr int QX = TOT < QMAX ? TOT : QMAX;
+    static constexpr int RP = R < 8 ? 8 : R;          // rank padded to one 16-byte piece
+    static constexpr int BP = (R < 16 ? 16 : R) + 8;  // LDS row pitch of a staged B slice (bf16), 16-byte pad
+    static constexpr int BMAX = 2;                    // B slices resident in LDS (more cost a workgroup per CU)
+    static constexpr int NB = NT < BMAX ? NT : BMAX;  // B slices resident
+    static constexpr int BV = kGemmTileRows * RP / 8;  // 16-byte pieces of one expert's B slice
+    static constexpr int BQ = (BV + 255) / 256;        // ... per thread
+    static_assert(NB >= 2 || NT == 1, "rolling needs two resident slices");
 };
 
-template <int R, class S>
+template <int R, int NT>
 __global__ __launch_bounds__(256) void switch_gemm_kernel(SwitchParams p)
+{
+    static_assert(R % 16 == 0 || R == 8 || R == 4, "rank: a multiple of 16, or 4 or 8 (zero padded)");
+    using P = GemmPlan<R, NT>;
+    constexpr int KCH = P::KCH, NCH = P::NCH, TOT = P::TOT, QX = P::QX, NB = P::NB;
+    constexpr int RP = P::RP, BP = P::BP, BV = P::BV, BQ = P::BQ;
+    constexpr bool kPadded = P::kPadded;
+    constexpr int TR = kGemmTileRows, TC = kGemmTileCols;
+    constexpr int WP = TC + 8;             // LDS row pitch of the W tile (bf16)
+    constexpr int WQ = TR * TC / 8 / 256;  // 16-byte pieces of the W tile per thread
+
+    __shared__ __align__(16) uint16_t s_b[NB][TR][BP];  // row operands of the resident experts
+    __shared__ __align__(16) uint16_t s_w[TR][WP];      // the W tile, on its way in and out
+
+    Terms terms;
+    if (!load_terms<NT>(p, terms)) return;
+    const int nt = p.inplace ? (p.mode == 2 ? 2 * p.k : p.k) : p.k;  // terms in use (the rest have coefficient 0)
+
+    const TileDev tile = p.tiles[blockIdx.x];
+    const MatDev m = p.mats[tile.mat];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wc = tid >> 6;   // the wave's 64-column strip
+    const int n = lane & 31;   // row inside a 32-row block (MFMA N index)
+    const int h = lane >> 5;   // which half of the k-step / of a 16-column group
+    const int lcol0 = 64 * wc;
+    const int rows_left = tile.rows_left, cols_left = tile.cols_left;
+    const int ldw = tile.ldw;
+
+    // ---- request everything, in the order of use
+    uint4_t wreg[WQ];
+#pragma unroll
+    for (int i = 0; i < WQ; ++i) {
+        const int q = tid + 256 * i;
+        const int row = q / (TC / 8), pc = q % (TC / 8);
+        const int cr = row < rows_left ? row : rows_left - 1;
+        const int cc = 8 * pc < cols_left ? 8 * pc : cols_left - 8;
+        wreg[i] = ld_global_nt(reinterpret_cast<const uint4_t *>(tile.w_src + (size_t)cr * ldw + cc));
+    }
+
+    auto fetch_b = [&](uint4_t (&v)[BQ], int e) {
+        const uint16_t *bsrc = m.b_bank + ((size_t)e * m.out + tile.row0) * R;
+#pragma unroll
+        for (int i = 0; i < BQ; ++i) {
+            const int q = tid + 256 * i;
+            const int row = q / (RP / 8), piece = q % (RP / 8);
+            const int cr = row < rows_left ? row : rows_left - 1;
+            if (q < BV) {
+                if constexpr (R >= 8) {
+                    v[i] = ld_global(reinterpret_cast<const uint4_t *>(bsrc + (size_t)cr * R + 8 * piece));
+                } else {  // rank 4: a row is 8 bytes
+                    const uint2_t t = ld_global(reinterpret_cast<const uint2_t *>(bsrc + (size_t)cr * R));
+                    v[i] = uint4_t{t[0], t[1], 0u, 0u};
+                }
+            }
+        }
+    };
+    auto stash_b = [&](const uint4_t (&v)[BQ], int slot) {
+#pragma unroll
+        for (int i = 0; i < BQ; ++i) {
+            const int q = tid + 256 * i;
+            const int row = q / (RP / 8), piece = q % (RP / 8);
+            if (q < BV) {
+                *reinterpret_cast<uint4_t *>(&s_b[slot][row][8 * piece]) = v[i];
+                if constexpr (kPadded)  // second half of the single k-step: zeros
+                    *reinterpret_cast<uint4_t *>(&s_b[slot][row][8]) = uint4_t{0u, 0u, 0u, 0u};
+            }
+        }
+    };
+
+    // column operand: the lane's column pair (clamped), 8 rank indices per k-step
+    int acol = lcol0 + 2 * n;
+    acol = tile.col0 + (acol < cols_left ? acol : cols_left - 2);
+    struct XChunk {
+        uint32_t d[KCH][8];
+    };
+    auto fetch_x = [&](XChunk &x, int e, int kc) {
+        if constexpr (kPadded) {
+            // rank indices 8h + i beyond R are zero: read a clamped index, then clear
+            const uint16_t *abase = m.a_bank + (size_t)e * R * m.in + acol;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int kap = 8 * h + i;
+                const uint32_t v = ld_global(reinterpret_cast<const uint32_t *>(abase + (size_t)(kap < R ? kap : R - 1) * m.in));
+                x.d[0][i] = kap < R ? v : 0u;
+            }
+        } else {
+            const uint16_t *abase = m.a_bank + ((size_t)e * R + 16 * KCH * kc + 8 * h) * m.in + acol;
+#pragma unroll
+            for (int s2 = 0; s2 < KCH; ++s2)
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    x.d[s2][i] = ld_global(reinterpret_cast<const uint32_t *>(abase + (size_t)(16 * s2 + i) * m.in));
+        }
+    };
+
+    uint4_t vb[NB][BQ];
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+        if (j < nt) fetch_b(vb[j], terms.e[j]);
+    XChunk xq[QX];
+#pragma unroll
+    for (int i = 0; i < QX; ++i)
+        if (i / NCH < nt) fetch_x(xq[i], terms.e[i / NCH], i % NCH);
+
+    // W tile and row operands into LDS as they land: the registers are free for the contraction
+#pragma unroll
+    for (int i = 0; i < WQ; ++i) {
+        const int q = tid + 256 * i;
+        *reinterpret_cast<uint4_t *>(&s_w[q / (TC / 8)][8 * (q % (TC / 8))]) = wreg[i];
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+        if (j < nt) stash_b(vb[j], j);
+    __syncthreads();
+
+    float16_t acc[2][2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.0f;
+
+    // ---- the contraction, fully unrolled over experts and chunks (all queue slots static)
+    float c_last = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+        const float c = terms.c[j];
+        const bool active = j < nt && c != 0.0f;  // uniform; a zero coefficient contributes nothing
+        uint4_t vroll[BQ];
+        if constexpr (NT > NB) {
+            if (j + NB < NT && j + NB < nt) fetch_b(vroll, terms.e[j + NB]);  // rolls into this expert's slot below
+        }
+        if (active && c_last != 0.0f) {
+            const float ratio = c_last / c;
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[rb][cb][v] *= ratio;
+        }
+        if (active) c_last = c;
+#pragma unroll
+        for (int kc = 0; kc < NCH; ++kc) {
+            const int i = j * NCH + kc;  // chunk number; a constant after unrolling
+            XChunk &x = xq[i % QX];
+            bf16x8_t x0[KCH], x1[KCH];
+#pragma unroll
+            for (int s2 = 0; s2 < KCH; ++s2) {
+                const uint32_t *d = x.d[s2];
+                const uint4_t xe = {__builtin_amdgcn_perm(d[1], d[0], 0x05040100u), __builtin_amdgcn_perm(d[3], d[2], 0x05040100u),
+                                    __builtin_amdgcn_perm(d[5], d[4], 0x05040100u), __builtin_amdgcn_perm(d[7], d[6], 0x05040100u)};
+                const uint4_t xo = {__builtin_amdgcn_perm(d[1], d[0], 0x07060302u), __builtin_amdgcn_perm(d[3], d[2], 0x07060302u),
+                                    __builtin_amdgcn_perm(d[5], d[4], 0x07060302u), __builtin_amdgcn_perm(d[7], d[6], 0x07060302u)};
+                x0[s2] = __builtin_bit_cast(bf16x8_t, xe);
+                x1[s2] = __builtin_bit_cast(bf16x8_t, xo);
+            }
+            // the slot is consumed: refill it with the chunk QX ahead
+            if (i + QX < TOT && (i + QX) / NCH < nt) fetch_x(x, terms.e[(i + QX) / NCH], (i + QX) % NCH);
+            if (active) {
+#pragma unroll
+                for (int s2 = 0; s2 < KCH; ++s2) {
+                    const int ks = kc * KCH + s2;
+#pragma unroll
+                    for (int rb = 0; rb < 2; ++rb) {
+                        const uint4_t y = *reinterpret_cast<const uint4_t *>(&s_b[j % NB][32 * rb + n][16 * ks + 8 * h]);
+                        const bf16x8_t yy = __builtin_bit_cast(bf16x8_t, y);
+                        acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0[s2], yy, acc[rb][0], 0, 0, 0);
+                        acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1[s2], yy, acc[rb][1], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        if constexpr (NT > NB) {
+            if (j + NB < NT) {
+                __syncthreads();  // every wave is done reading this expert's slot ...
+                if (j + NB < nt) stash_b(vroll, j % NB);
+                // ... and the refill is complete before expert j + NB reads it: the barrier
+                // after expert j + 1 (NB >= 2) orders it, or, for the last refill, this one
+                if (j + NB + 1 >= NT) __syncthreads();
+            }
+        }
+    }
+
+    // ---- epilogue: each lane updates its pieces of the W tile in LDS, in the result
+    // layout (column p of a group is accumulator cb = p&1, v = 4b + p/2); tile back out.
+    if (nt > 0) {  // nothing selected (un-merge out of place): the bits pass through untouched
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                uint4_t *slot = reinterpret_cast<uint4_t *>(&s_w[32 * rb + n][lcol0 + 16 * b + 8 * h]);
+                const uint4_t wv = *slot;
+                float o[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) o[q] = c_last * acc[rb][q & 1][4 * b + (q >> 1)];
+                uint4_t out;
+#pragma unroll
+                for (int hh = 0; hh < 4; ++hh)
+                    out[hh] = pack_bf16_rne(o[2 * hh] + bf16_lo(wv[hh]), o[2 * hh + 1] + bf16_hi(wv[hh]));
+                *slot = out;
+            }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < WQ; ++i) {
+        const int q = tid + 256 * i;
+        const int row = q / (TC / 8), pc = q % (TC / 8);
+        if (row < rows_left && 8 * pc < cols_left)
+            st_global_nt(*reinterpret_cast<const uint4_t *>(&s_w[row][8 * pc]),
+                         reinterpret_cast<uint4_t *>(tile.w_dst + (size_t)row * ldw + 8 * pc));
+    }
+}
+
+// The same kernel for many experts (4 or more terms): a run-time loop over the
+// experts with the term list in LDS, one barrier per expert, the next expert's
+// row operand and the next column-operand chunk in flight.  Unrolling the
+// expert loop (as above) costs registers here, and with them a workgroup per CU,
+// which matters more than prefetch depth: this kernel is bound by latency per
+// workgroup.
+template <int R>
+__global__ __launch_bounds__(256) void switch_gemm_loop_kernel(SwitchParams p)
 {
     static_assert(R % 16 == 0 || R == 8 || R == 4, "rank must be a multiple of the MFMA depth, or 4 or 8 (zero padded)");
     constexpr int KS = (R + 15) / 16;   // k-steps per expert
     constexpr bool kPadded = R < 16;    // one k-step whose rank indices >= R are zero
-    constexpr int TR = S::TR;           // tile rows
+    constexpr int TR = kGemmTileRows;   // tile rows
     constexpr int RP = R < 8 ? 8 : R;   // rank padded to one 16-byte piece
     constexpr int BP = (R < 16 ? 16 : R) + 8;  // LDS row pitch of the staged B slice (bf16): 16-byte pad against bank conflicts
     constexpr int BV = TR * RP / 8;     // 16-byte pieces of one expert's B slice for the tile
     constexpr int BQ = (BV + 255) / 256;  // ... per thread
-    constexpr int TC = S::TC;           // tile columns
+    constexpr int TC = kGemmTileCols;   // tile columns
     constexpr int WP = TC + 8;          // LDS row pitch of the W tile (bf16)
     constexpr int WQ = TR * TC / 8 / 256;  // 16-byte pieces of the W tile per thread
 
@@ -78,12 +324,12 @@ __global__ __launch_bounds__(256) void switch_gemm_kernel(SwitchParams p)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wr = wave / S::WCW, wc = wave % S::WCW;
+    const int wr = 0, wc = wave;
     const int n = lane & 31;   // row inside a 32-row block (MFMA N index)
     const int h = lane >> 5;   // which half of the k-step / of a 16-column group
 
-    const int lrow0 = kGemmWaveRows * wr;              // wave origin inside the tile
-    const int lcol0 = kGemmWaveCols * wc;
+    const int lrow0 = 64 * wr;                         // wave origin inside the tile
+    const int lcol0 = 64 * wc;
     const int rows_left = tile.rows_left, cols_left = tile.cols_left;
     const int ldw = tile.ldw;
 
