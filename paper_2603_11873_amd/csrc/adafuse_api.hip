@@ -24,7 +24,7 @@ struct adafuse_ctx {
     int32_t tile_rows = 0, tile_cols = 0;
     int32_t mfma_shape = 0;  // index into the matrix-core kernel's tile shapes
     bool inplace = false;    // every matrix has w_work == w_base
-    int32_t order = 128;     // tiles per XCD run (ADAFUSE_ORDER; 0 = plain order, 1 = an eighth of the list)
+    int32_t order = 512;     // tiles per XCD run (ADAFUSE_ORDER; 0 = plain order, 1 = an eighth of the list)
     int64_t n_tiles = 0, elements = 0;
     int device = -1;
     MatDev *d_mats = nullptr;
