@@ -23,6 +23,7 @@ struct adafuse_ctx {
     int32_t kernel = ADAFUSE_KERNEL_VALU;  // kernel in effect, never AUTO
     int32_t tile_rows = 0, tile_cols = 0;
     int32_t mfma_shape = 0;  // index into the matrix-core kernel's tile shapes
+    int32_t gemm_waves = 4;  // waves per workgroup of the rank-looped kernel: tile 64 x (64 waves)
     bool inplace = false;    // every matrix has w_work == w_base
     int32_t order = 512;     // tiles per XCD run (ADAFUSE_ORDER; 0 = plain order, 1 = an eighth of the list)
     int64_t n_tiles = 0, elements = 0;
@@ -126,28 +127,35 @@ bool launch_mfma_any(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t
     }
 }
 
-template <int R>
-bool launch_gemm_r(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t s)
+template <int R, int NW>
+bool launch_gemm_rw(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t s)
 {
+    const dim3 grid((unsigned)n_tiles), block(64 * NW);
     switch (nt) {
-    case 1: hipLaunchKernelGGL((switch_gemm_kernel<R, 1>), dim3((unsigned)n_tiles), dim3(256), 0, s, p); return true;
-    case 2: hipLaunchKernelGGL((switch_gemm_kernel<R, 2>), dim3((unsigned)n_tiles), dim3(256), 0, s, p); return true;
+    case 1: hipLaunchKernelGGL((switch_gemm_kernel<R, 1, NW>), grid, block, 0, s, p); return true;
+    case 2: hipLaunchKernelGGL((switch_gemm_kernel<R, 2, NW>), grid, block, 0, s, p); return true;
     case 4:
-    case 8: hipLaunchKernelGGL((switch_gemm_loop_kernel<R>), dim3((unsigned)n_tiles), dim3(256), 0, s, p); return true;
+    case 8: hipLaunchKernelGGL((switch_gemm_loop_kernel<R, NW>), grid, block, 0, s, p); return true;
     default: return false;
     }
 }
 
-// nt = term bucket (1, 2, 4 or 8)
-bool launch_gemm(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t s)
+template <int R>
+bool launch_gemm_r(const SwitchParams &p, int nt, int waves, int64_t n_tiles, hipStream_t s)
+{
+    return waves == 8 ? launch_gemm_rw<R, 8>(p, nt, n_tiles, s) : launch_gemm_rw<R, 4>(p, nt, n_tiles, s);
+}
+
+// nt = term bucket (1, 2, 4 or 8); waves = 4 or 8 per workgroup (tile 64 x 64 waves)
+bool launch_gemm(const SwitchParams &p, int nt, int waves, int64_t n_tiles, hipStream_t s)
 {
     switch (p.r) {
-    case 4: return launch_gemm_r<4>(p, nt, n_tiles, s);
-    case 8: return launch_gemm_r<8>(p, nt, n_tiles, s);
-    case 16: return launch_gemm_r<16>(p, nt, n_tiles, s);
-    case 32: return launch_gemm_r<32>(p, nt, n_tiles, s);
-    case 64: return launch_gemm_r<64>(p, nt, n_tiles, s);
-    case 128: return launch_gemm_r<128>(p, nt, n_tiles, s);
+    case 4: return launch_gemm_r<4>(p, nt, waves, n_tiles, s);
+    case 8: return launch_gemm_r<8>(p, nt, waves, n_tiles, s);
+    case 16: return launch_gemm_r<16>(p, nt, waves, n_tiles, s);
+    case 32: return launch_gemm_r<32>(p, nt, waves, n_tiles, s);
+    case 64: return launch_gemm_r<64>(p, nt, waves, n_tiles, s);
+    case 128: return launch_gemm_r<128>(p, nt, waves, n_tiles, s);
     default: return false;
     }
 }
@@ -240,8 +248,9 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
             return true;
         });
     } else if (kernel == ADAFUSE_KERNEL_GEMM) {
+        if (const char *e = std::getenv("ADAFUSE_GEMM_WAVES")) c->gemm_waves = std::atoi(e) == 8 ? 8 : 4;
         tr = kGemmTileRows;
-        tc = kGemmTileCols;
+        tc = kGemmWaveCols * c->gemm_waves;
     }
     std::vector<MatDev> hm(c->mats.size());
     std::vector<TileDev> ht;
@@ -425,7 +434,7 @@ adafuse_status switch_launches(adafuse_ctx *ctx, const int32_t *idx_prev, const 
             if (!launched) return ADAFUSE_ERR_ARG;
         } else if (ctx->kernel == ADAFUSE_KERNEL_GEMM) {
             // the copy (nothing selected) runs through the one-term instance
-            if (!launch_gemm(p, terms_bucket(n_terms > 0 ? n_terms : 1), count, s)) return ADAFUSE_ERR_ARG;
+            if (!launch_gemm(p, terms_bucket(n_terms > 0 ? n_terms : 1), ctx->gemm_waves, count, s)) return ADAFUSE_ERR_ARG;
         } else {
             hipLaunchKernelGGL(switch_valu_kernel, dim3((unsigned)count), dim3(256), valu_lds, s, p);
         }

@@ -45,7 +45,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float float16_t;
 
 constexpr int kGemmTileRows = 64;
-constexpr int kGemmTileCols = 256;
+constexpr int kGemmWaveCols = 64;  // a workgroup of NW waves covers 64 NW columns
 
 template <int R, int NT>
 struct GemmPlan {
@@ -61,21 +61,22 @@ struct GemmPlan {
     static constexpr int BMAX = 2;                    // B slices resident in LDS (more cost a workgroup per CU)
     static constexpr int NB = NT < BMAX ? NT : BMAX;  // B slices resident
     static constexpr int BV = kGemmTileRows * RP / 8;  // 16-byte pieces of one expert's B slice
-    static constexpr int BQ = (BV + 255) / 256;        // ... per thread
+    static constexpr int BQ(int nthr) { return (BV + nthr - 1) / nthr; }  // ... per thread
     static_assert(NB >= 2 || NT == 1, "rolling needs two resident slices");
 };
 
-template <int R, int NT>
-__global__ __launch_bounds__(256) void switch_gemm_kernel(SwitchParams p)
+template <int R, int NT, int NW>
+__global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
 {
     static_assert(R % 16 == 0 || R == 8 || R == 4, "rank: a multiple of 16, or 4 or 8 (zero padded)");
     using P = GemmPlan<R, NT>;
+    constexpr int NTHR = 64 * NW;
     constexpr int KCH = P::KCH, NCH = P::NCH, TOT = P::TOT, QX = P::QX, NB = P::NB;
-    constexpr int RP = P::RP, BP = P::BP, BV = P::BV, BQ = P::BQ;
+    constexpr int RP = P::RP, BP = P::BP, BV = P::BV, BQ = P::BQ(NTHR);
     constexpr bool kPadded = P::kPadded;
-    constexpr int TR = kGemmTileRows, TC = kGemmTileCols;
-    constexpr int WP = TC + 8;             // LDS row pitch of the W tile (bf16)
-    constexpr int WQ = TR * TC / 8 / 256;  // 16-byte pieces of the W tile per thread
+    constexpr int TR = kGemmTileRows, TC = kGemmWaveCols * NW;
+    constexpr int WP = TC + 8;              // LDS row pitch of the W tile (bf16)
+    constexpr int WQ = TR * TC / 8 / NTHR;  // 16-byte pieces of the W tile per thread
 
     __shared__ __align__(16) uint16_t s_b[NB][TR][BP];  // row operands of the resident experts
     __shared__ __align__(16) uint16_t s_w[TR][WP];      // the W tile, on its way in and out
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(256) void switch_gemm_kernel(SwitchParams p)
     uint4_t wreg[WQ];
 #pragma unroll
     for (int i = 0; i < WQ; ++i) {
-        const int q = tid + 256 * i;
+        const int q = tid + NTHR * i;
         const int row = q / (TC / 8), pc = q % (TC / 8);
         const int cr = row < rows_left ? row : rows_left - 1;
         const int cc = 8 * pc < cols_left ? 8 * pc : cols_left - 8;
@@ -110,7 +111,7 @@ __global__ __launch_bounds__(256) void switch_gemm_kernel(SwitchParams p)
         const uint16_t *bsrc = m.b_bank + ((size_t)e * m.out + tile.row0) * R;
 #pragma unroll
         for (int i = 0; i < BQ; ++i) {
-            const int q = tid + 256 * i;
+            const int q = tid + NTHR * i;
             const int row = q / (RP / 8), piece = q % (RP / 8);
             const int cr = row < rows_left ? row : rows_left - 1;
             if (q < BV) {
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(256) void switch_gemm_kernel(SwitchParams p)
     auto stash_b = [&](const uint4_t (&v)[BQ], int slot) {
 #pragma unroll
         for (int i = 0; i < BQ; ++i) {
-            const int q = tid + 256 * i;
+            const int q = tid + NTHR * i;
             const int row = q / (RP / 8), piece = q % (RP / 8);
             if (q < BV) {
                 *reinterpret_cast<uint4_t *>(&s_b[slot][row][8 * piece]) = v[i];
@@ -174,7 +175,7 @@ __global__ __launch_bounds__(256) void switch_gemm_kernel(SwitchParams p)
     // W tile and row operands into LDS as they land: the registers are free for the contraction
 #pragma unroll
     for (int i = 0; i < WQ; ++i) {
-        const int q = tid + 256 * i;
+        const int q = tid + NTHR * i;
         *reinterpret_cast<uint4_t *>(&s_w[q / (TC / 8)][8 * (q % (TC / 8))]) = wreg[i];
     }
 #pragma unroll
@@ -274,7 +275,7 @@ __global__ __launch_bounds__(256) void switch_gemm_kernel(SwitchParams p)
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < WQ; ++i) {
-        const int q = tid + 256 * i;
+        const int q = tid + NTHR * i;
         const int row = q / (TC / 8), pc = q % (TC / 8);
         if (row < rows_left && 8 * pc < cols_left)
             st_global_nt(*reinterpret_cast<const uint4_t *>(&s_w[row][8 * pc]),
@@ -288,8 +289,8 @@ __global__ __launch_bounds__(256) void switch_gemm_kernel(SwitchParams p)
 // expert loop (as above) costs registers here, and with them a workgroup per CU,
 // which matters more than prefetch depth: this kernel is bound by latency per
 // workgroup.
-template <int R>
-__global__ __launch_bounds__(256) void switch_gemm_loop_kernel(SwitchParams p)
+template <int R, int NW>
+__global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams p)
 {
     static_assert(R % 16 == 0 || R == 8 || R == 4, "rank must be a multiple of the MFMA depth, or 4 or 8 (zero padded)");
     constexpr int KS = (R + 15) / 16;   // k-steps per expert
@@ -298,10 +299,11 @@ __global__ __launch_bounds__(256) void switch_gemm_loop_kernel(SwitchParams p)
     constexpr int RP = R < 8 ? 8 : R;   // rank padded to one 16-byte piece
     constexpr int BP = (R < 16 ? 16 : R) + 8;  // LDS row pitch of the staged B slice (bf16): 16-byte pad against bank conflicts
     constexpr int BV = TR * RP / 8;     // 16-byte pieces of one expert's B slice for the tile
-    constexpr int BQ = (BV + 255) / 256;  // ... per thread
-    constexpr int TC = kGemmTileCols;   // tile columns
+    constexpr int BQ = (BV + 64 * NW - 1) / (64 * NW);  // ... per thread
+    constexpr int NTHR = 64 * NW;
+    constexpr int TC = kGemmWaveCols * NW;  // tile columns
     constexpr int WP = TC + 8;          // LDS row pitch of the W tile (bf16)
-    constexpr int WQ = TR * TC / 8 / 256;  // 16-byte pieces of the W tile per thread
+    constexpr int WQ = TR * TC / 8 / (64 * NW);  // 16-byte pieces of the W tile per thread
 
     __shared__ int32_t s_e[kMaxTerms];
     __shared__ float s_c[kMaxTerms];
@@ -342,7 +344,7 @@ __global__ __launch_bounds__(256) void switch_gemm_loop_kernel(SwitchParams p)
     uint4_t wreg[WQ];
 #pragma unroll
     for (int i = 0; i < WQ; ++i) {
-        const int q = tid + 256 * i;
+        const int q = tid + NTHR * i;
         const int row = q / (TC / 8), pc = q % (TC / 8);
         const int cr = row < rows_left ? row : rows_left - 1;
         const int cc = 8 * pc < cols_left ? 8 * pc : cols_left - 8;
@@ -370,7 +372,7 @@ __global__ __launch_bounds__(256) void switch_gemm_loop_kernel(SwitchParams p)
         const uint16_t *bsrc = m.b_bank + ((size_t)e * m.out + tile.row0) * R;
 #pragma unroll
         for (int i = 0; i < BQ; ++i) {
-            const int q = tid + 256 * i;
+            const int q = tid + NTHR * i;
             const int row = q / (RP / 8), piece = q % (RP / 8);
             const int cr = row < rows_left ? row : rows_left - 1;
             if (q < BV) {
@@ -386,7 +388,7 @@ __global__ __launch_bounds__(256) void switch_gemm_loop_kernel(SwitchParams p)
     auto stash_b = [&](const uint4_t (&v)[BQ], int buf) {
 #pragma unroll
         for (int i = 0; i < BQ; ++i) {
-            const int q = tid + 256 * i;
+            const int q = tid + NTHR * i;
             const int row = q / (RP / 8), piece = q % (RP / 8);
             if (q < BV) {
                 *reinterpret_cast<uint4_t *>(&s_b[buf][row][8 * piece]) = v[i];
@@ -442,7 +444,7 @@ __global__ __launch_bounds__(256) void switch_gemm_loop_kernel(SwitchParams p)
     // the registers are free for the contraction
 #pragma unroll
     for (int i = 0; i < WQ; ++i) {
-        const int q = tid + 256 * i;
+        const int q = tid + NTHR * i;
         *reinterpret_cast<uint4_t *>(&s_w[q / (TC / 8)][8 * (q % (TC / 8))]) = wreg[i];
     }
     if (j < nt) stash_b(vb, 0);
@@ -518,7 +520,7 @@ __global__ __launch_bounds__(256) void switch_gemm_loop_kernel(SwitchParams p)
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < WQ; ++i) {
-        const int q = tid + 256 * i;
+        const int q = tid + NTHR * i;
         const int row = q / (TC / 8), pc = q % (TC / 8);
         if (row < rows_left && 8 * pc < cols_left)
             st_global_nt(*reinterpret_cast<const uint4_t *>(&s_w[row][8 * pc]),
