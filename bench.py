@@ -36,6 +36,8 @@ def parse_args():
                     help="paper-literal in-place update (w_work == w_base): SWAP carries 2k experts")
     ap.add_argument("--per-matrix", action="store_true",
                     help="the paper's 'simple merge' ablation: one launch per adapted matrix instead of one for all")
+    ap.add_argument("--forward", action="store_true",
+                    help="also time the step after the switch: merged GEMVs vs the un-merged dynamic-adapter path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=2, help="layers of the model the oracle is timed on")
     return ap.parse_args()
@@ -74,6 +76,30 @@ def cpu_baseline(wl, mats, hidden, router, t, n_layers):
     return {"value": full * 1e6, "unit": "us/token", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"one switch of the first {n_layers} of {wl.layers} layers ({len(host)} matrices, "
                       f"{elems} elements) in {dt:.2f} s, scaled by element count to the full model"}
+
+
+def forward_context(torch, af, ctx, wl, mats, idx, gates, stream, reps=20):
+    """us per token of one pass over all matrices: merged backbone (Eq.3) and dynamic adapters (Eq.2)."""
+    dev = mats[0][0].device
+    x = torch.randn(sum(m[0].shape[1] for m in mats), device=dev).to(torch.bfloat16)
+    y = torch.zeros(sum(m[0].shape[0] for m in mats), dtype=torch.float32, device=dev)
+    z = torch.zeros(wl.k * wl.r, dtype=torch.float32, device=dev)
+    hi, hg = idx[0].cpu().tolist(), gates[0].cpu().tolist()
+    res = {}
+    with torch.cuda.stream(stream):
+        for name, fn in (("merged_gemv", lambda: ctx.forward_merged(x, y, stream=stream)),
+                         ("dynamic_adapter", lambda: ctx.forward_dynamic(hi, hg, wl.scale, x, y, z, stream=stream))):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            res[name + "_us"] = (time.perf_counter() - t0) / reps * 1e6
+    res["launches"] = {"merged_gemv": wl.n_mats, "dynamic_adapter": wl.n_mats * (1 + 2 * wl.k)}
+    res["note"] = "one GEMV per matrix; the dynamic form adds a down- and an up-projection launch per selected expert"
+    return res
 
 
 def main():
@@ -172,6 +198,8 @@ def main():
                      "kernel_us": {"mean": avg_kernel_s * 1e6, "median": srt[len(srt) // 2] * 1e3,
                                    "p95": srt[int(0.95 * (len(srt) - 1))] * 1e3, "min": srt[0] * 1e3}},
     }
+    if args.forward and not args.inplace:
+        out["decode_context"] = forward_context(torch, af, ctx, wl, mats, idx, gates, stream)
     if not args.no_cpu_baseline:
         t = (args.warmup + args.steps - 1) % T
         out["cpu_baseline"] = cpu_baseline(wl, mats, hidden, router, t, min(args.cpu_layers, wl.layers))

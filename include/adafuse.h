@@ -188,6 +188,29 @@ adafuse_status adafuse_switch_per_matrix(adafuse_ctx *ctx,
                                          const int32_t *idx_next, const float *gates_next,
                                          int32_t k, float scale, int32_t mode, void *hip_stream);
 
+/*
+ * The step right AFTER the switch, provided for checking and for context, not as
+ * a product path: every matrix of the context applied to one token's input, as a
+ * decode loop launches it.
+ *   adafuse_forward_merged   y_m = W_work,m x_m                      (Eq.3: the merged backbone)
+ *   adafuse_forward_dynamic  y_m = W_base,m x_m + s * sum_j g_j B_{e_j}(A_{e_j} x_m)
+ *                            (Eq.2 at run time: per matrix one GEMV plus, per
+ *                            selected expert, a down- and an up-projection launch
+ *                            -- the "four or more additional kernel calls" of a
+ *                            dynamic adapter layer)
+ * x  DEVICE bf16: the inputs of all matrices, concatenated in matrix order
+ *    (in_0 + in_1 + ... elements; each `in` is a multiple of 8, so every piece is
+ *    16-byte aligned if x is);  y  DEVICE fp32: the outputs, concatenated
+ *    (out_0 + out_1 + ...).  fp32 accumulation.
+ * adafuse_forward_dynamic takes the routing decision from HOST arrays idx[k],
+ * gates[k] (a dynamic adapter decides on the host which experts to launch) and a
+ * DEVICE scratch z of k*r floats owned by the caller; it needs an out-of-place
+ * context.  n_mats (merged) or n_mats*(1+2k) (dynamic) launches on `hip_stream`.
+ */
+adafuse_status adafuse_forward_merged(adafuse_ctx *ctx, const void *x, float *y, void *hip_stream);
+adafuse_status adafuse_forward_dynamic(adafuse_ctx *ctx, const int32_t *idx, const float *gates, int32_t k,
+                                       float scale, const void *x, float *y, float *z, void *hip_stream);
+
 const char *adafuse_status_string(int32_t status);
 
 #ifdef __cplusplus

@@ -11,7 +11,8 @@ GATE_SOFTMAX_OVER_TOPK, GATE_TOPK_OF_SOFTMAX = 0, 1
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_GEMM = 0, 1, 2, 3
 
 EXPORTS = ["adafuse_create", "adafuse_destroy", "adafuse_set_kernel", "adafuse_get_info",
-           "adafuse_pregate", "adafuse_fused_switch", "adafuse_switch_per_matrix", "adafuse_status_string"]
+           "adafuse_pregate", "adafuse_fused_switch", "adafuse_switch_per_matrix", "adafuse_forward_merged", "adafuse_forward_dynamic",
+           "adafuse_status_string"]
 
 
 class AdafuseError(RuntimeError):
@@ -62,6 +63,10 @@ def load_library():
     L.adafuse_fused_switch.argtypes = [vp, vp, vp, vp, vp, i32, f32, i32, vp]
     L.adafuse_switch_per_matrix.restype = i32
     L.adafuse_switch_per_matrix.argtypes = [vp, vp, vp, vp, vp, i32, f32, i32, vp]
+    L.adafuse_forward_merged.restype = i32
+    L.adafuse_forward_merged.argtypes = [vp, vp, vp, vp]
+    L.adafuse_forward_dynamic.restype = i32
+    L.adafuse_forward_dynamic.argtypes = [vp, C.POINTER(i32), C.POINTER(f32), i32, f32, vp, vp, vp, vp]
     L.adafuse_status_string.restype = C.c_char_p
     L.adafuse_status_string.argtypes = [i32]
     _lib = L
@@ -160,6 +165,22 @@ class Context:
                                                       _ptr(gates_next), k, scale, mode, _stream_handle(stream))
         if st != 0:
             raise AdafuseError(st, "adafuse_switch_per_matrix")
+
+    def forward_merged(self, x, y, stream=None):
+        """adafuse_forward_merged: y_m = W_work,m x_m for every matrix (x bf16, y fp32, concatenated)."""
+        st = load_library().adafuse_forward_merged(self._h, _ptr(x), _ptr(y), _stream_handle(stream))
+        if st != 0:
+            raise AdafuseError(st, "adafuse_forward_merged")
+
+    def forward_dynamic(self, idx, gates, scale, x, y, z, stream=None):
+        """adafuse_forward_dynamic: the un-merged adapter path; idx/gates are host sequences."""
+        k = len(idx)
+        ci = (C.c_int32 * k)(*[int(v) for v in idx])
+        cg = (C.c_float * k)(*[float(v) for v in gates])
+        st = load_library().adafuse_forward_dynamic(self._h, ci, cg, k, scale, _ptr(x), _ptr(y), _ptr(z),
+                                                    _stream_handle(stream))
+        if st != 0:
+            raise AdafuseError(st, "adafuse_forward_dynamic")
 
     def close(self):
         if self._h:

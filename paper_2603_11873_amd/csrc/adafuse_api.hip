@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "device_types.hpp"
+#include "forward.hpp"
 #include "pregate.hpp"
 #include "switch_gemm.hpp"
 #include "switch_mfma.hpp"
@@ -456,6 +457,50 @@ adafuse_status adafuse_switch_per_matrix(adafuse_ctx *ctx, const int32_t *idx_pr
                                          int32_t mode, void *hip_stream)
 {
     return switch_launches(ctx, idx_prev, gates_prev, idx_next, gates_next, k, scale, mode, hip_stream, true);
+}
+
+adafuse_status adafuse_forward_merged(adafuse_ctx *ctx, const void *x, float *y, void *hip_stream)
+{
+    if (!ctx || !x || !y) return ADAFUSE_ERR_NULL;
+    if (!aligned16(x)) return ADAFUSE_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const uint16_t *xp = static_cast<const uint16_t *>(x);
+    for (const adafuse_matrix_desc &m : ctx->mats) {
+        hipLaunchKernelGGL(gemv_rows_kernel, dim3((unsigned)((m.out + 3) / 4)), dim3(256), 0, s,
+                           static_cast<const uint16_t *>(m.w_work), (int64_t)m.ldw, xp, y, m.out, m.in);
+        xp += m.in;
+        y += m.out;
+    }
+    return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
+}
+
+adafuse_status adafuse_forward_dynamic(adafuse_ctx *ctx, const int32_t *idx_host, const float *gates_host, int32_t k,
+                                       float scale, const void *x, float *y, float *z, void *hip_stream)
+{
+    if (!ctx || !idx_host || !gates_host || !x || !y || !z) return ADAFUSE_ERR_NULL;
+    if (k < 1 || k > ctx->k_max) return ADAFUSE_ERR_ARG;
+    for (int j = 0; j < k; ++j)
+        if (idx_host[j] < 0 || idx_host[j] >= ctx->E) return ADAFUSE_ERR_ARG;
+    if (ctx->inplace) return ADAFUSE_ERR_ARG;  // needs the unmodified base weights
+    if (!aligned16(x)) return ADAFUSE_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const uint16_t *xp = static_cast<const uint16_t *>(x);
+    const int r = ctx->r;
+    for (const adafuse_matrix_desc &m : ctx->mats) {
+        hipLaunchKernelGGL(gemv_rows_kernel, dim3((unsigned)((m.out + 3) / 4)), dim3(256), 0, s,
+                           static_cast<const uint16_t *>(m.w_base), (int64_t)m.ldw, xp, y, m.out, m.in);
+        for (int j = 0; j < k; ++j) {
+            const uint16_t *a = static_cast<const uint16_t *>(m.a_bank) + (size_t)idx_host[j] * r * m.in;
+            const uint16_t *b = static_cast<const uint16_t *>(m.b_bank) + (size_t)idx_host[j] * m.out * r;
+            hipLaunchKernelGGL(gemv_rows_kernel, dim3((unsigned)((r + 3) / 4)), dim3(256), 0, s, a, (int64_t)m.in, xp,
+                               z + (size_t)j * r, r, m.in);
+            hipLaunchKernelGGL(lora_up_kernel, dim3((unsigned)((m.out + 255) / 256)), dim3(256), 0, s, b,
+                               z + (size_t)j * r, y, m.out, r, scale * gates_host[j]);
+        }
+        xp += m.in;
+        y += m.out;
+    }
+    return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
 }
 
 const char *adafuse_status_string(int32_t status)

@@ -107,5 +107,7 @@ def test_pregate_rejects_bad_arguments(L):
 def test_switch_and_misc_reject_null_context(L):
     assert L.adafuse_fused_switch(None, None, None, None, None, 2, 2.0, 0, None) == ERR_NULL
     assert L.adafuse_switch_per_matrix(None, None, None, None, None, 2, 2.0, 0, None) == ERR_NULL
+    assert L.adafuse_forward_merged(None, None, None, None) == ERR_NULL
+    assert L.adafuse_forward_dynamic(None, None, None, 2, 2.0, None, None, None, None) == ERR_NULL
     assert L.adafuse_set_kernel(None, 1) == ERR_NULL
     assert L.adafuse_get_info(None, None) == ERR_NULL

@@ -547,3 +547,56 @@ def test_rank_looped_kernel_modes(oracle, r, k, inplace):
             assert torch.equal(m[1].view(torch.int16), wb.view(torch.int16))
     tally.finish(MAX_DIFF_FRACTION)
     ctx.close()
+
+
+# ---- the step after the switch: merged GEMV versus the un-merged dynamic-adapter path -------
+
+@pytest.mark.parametrize("name,layers", [("toy", 2), ("llama2_7b_all", 1)])
+def test_merged_forward_equals_dynamic_adapter_forward(oracle, name, layers):
+    """Eq.2 (adapter applied at run time) against Eq.3 (merged backbone), on the device, and both
+    against the oracle: y = W' x with W' from the GPU switch, y = W x + s sum g B(A x) from base."""
+    wl = wlmod.scaled_down(wlmod.WORKLOADS[name], layers)
+    m = DeviceModel(wl, gen_device="cpu" if name == "toy" else "cuda")
+    dev = m.hidden.device
+    hidx, hg, idx, gates = oracle_decisions(oracle, m.hidden, m.router, wl.k)
+    t = 3
+    m.ctx.fused_switch(None, None, idx[t], gates[t], wl.k, wl.scale, af.MERGE)
+    g = torch.Generator().manual_seed(5)
+    xs = [torch.randn(wb.shape[1], generator=g).to(torch.bfloat16) for wb, _, _, _ in m.mats]
+    x = torch.cat(xs).to(dev)
+    n_out = sum(wb.shape[0] for wb, _, _, _ in m.mats)
+    y_m = torch.zeros(n_out, dtype=torch.float32, device=dev)
+    y_d = torch.zeros(n_out, dtype=torch.float32, device=dev)
+    z = torch.zeros(wl.k * wl.r, dtype=torch.float32, device=dev)
+    y_b = torch.zeros(n_out, dtype=torch.float32, device=dev)
+    m.ctx.forward_merged(x, y_m)
+    m.ctx.forward_dynamic(hidx[t], hg[t], wl.scale, x, y_d, z)
+    m.ctx.fused_switch(None, None, None, None, wl.k, wl.scale, af.UNMERGE)     # W_work = W_base, bit for bit
+    m.ctx.forward_merged(x, y_b)
+    _sync()
+    y_m, y_d, y_b = (v.cpu().numpy().astype(np.float64) for v in (y_m, y_d, y_b))
+    o = 0
+    for (wb, ww, a, b), xv in zip(m.mats, xs):
+        out = wb.shape[0]
+        xd = xv.double().numpy()
+        wbits, abits, bbits = wlmod.bits(wb), wlmod.bits(a), wlmod.bits(b)
+        merged = oracle.merge(wbits, abits, bbits, hidx[t], hg[t], wl.scale)           # the oracle's own W'
+        wv = np.abs(wlmod.from_bits(merged).double().numpy())
+        mag = wv @ np.abs(xd)                                                          # sum |w||x| per row
+        spacing = 2.0 ** (np.floor(np.log2(np.maximum(wv, 2.0 ** -126))) - 7)
+        # the GEMV itself, on weights both sides know to the bit (fp32 accumulation: 1e-5 of sum |w||x|)
+        assert np.all(np.abs(y_b[o:o + out] - oracle.gemv_bf16(wbits, xd)) <= 1e-5 * mag)
+        # the dynamic-adapter path (base weights and banks only)
+        ref_d = oracle.dynamic_adapter_forward(wbits, abits, bbits, hidx[t], hg[t], wl.scale, xd)
+        assert np.all(np.abs(y_d[o:o + out] - ref_d) <= 1e-5 * mag)
+        # the merged backbone: the GPU's W' may differ from the oracle's by one spacing on a few
+        # rounding near-ties (the switch's own bar), each worth spacing * |x| in the output
+        ref_m = oracle.gemv_bf16(merged, xd)
+        flips = 2 * np.max(spacing * np.abs(xd), axis=1)
+        assert np.all(np.abs(y_m[o:o + out] - ref_m) <= 1e-5 * mag + flips)
+        # Eq.3 against Eq.2: the two outputs differ by the bf16 rounding of the merged weights only
+        bound = 0.5 * (2 * spacing) @ np.abs(xd) + 2e-5 * mag
+        assert np.all(np.abs(y_m[o:o + out] - y_d[o:o + out]) <= bound)
+        assert np.max(np.abs(y_m[o:o + out] - y_d[o:o + out])) > 0
+        o += out
+    m.close()
