@@ -167,8 +167,9 @@ adafuse_status adafuse_pregate(const void *hidden, const void *w_router,
  * slices are staged in registers and LDS.  Expert indices outside [0,E) in device memory are
  * clamped into range, not detected.  The call enqueues on `hip_stream` and
  * returns; no host synchronisation.
- * Errors: NULL ctx or a NULL pointer the mode needs -> ERR_NULL; bad k or mode ->
- * ERR_ARG; launch failure -> ERR_HIP.
+ * Errors: NULL ctx or a NULL pointer the mode needs -> ERR_NULL; bad k or mode, or a
+ * current device other than the one the context was created on -> ERR_ARG; launch
+ * failure -> ERR_HIP.
  */
 adafuse_status adafuse_fused_switch(adafuse_ctx *ctx,
                                     const int32_t *idx_prev, const float *gates_prev,

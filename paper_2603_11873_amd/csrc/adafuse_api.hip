@@ -200,6 +200,14 @@ int32_t auto_kernel(int r, int n_terms)
     return ADAFUSE_KERNEL_VALU;
 }
 
+// The tables live on the device that was current at adafuse_create; a launch
+// from another device would hand the kernels pointers they cannot use.
+bool on_ctx_device(const adafuse_ctx *c)
+{
+    int dev = -1;
+    return hipGetDevice(&dev) == hipSuccess && dev == c->device;
+}
+
 // Largest term count a launch of this context can carry.
 int max_terms(const adafuse_ctx *c) { return c->inplace ? 2 * c->k_max : c->k_max; }
 
@@ -410,6 +418,7 @@ adafuse_status switch_launches(adafuse_ctx *ctx, const int32_t *idx_prev, const 
     if (need_prev && (!idx_prev || !gates_prev)) return ADAFUSE_ERR_NULL;
     if ((idx_prev == nullptr) != (gates_prev == nullptr)) return ADAFUSE_ERR_NULL;
     if ((need_next || need_prev) && (k < 1 || k > ctx->k_max)) return ADAFUSE_ERR_ARG;
+    if (!on_ctx_device(ctx)) return ADAFUSE_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const bool copy_only = !ctx->inplace && mode == ADAFUSE_UNMERGE;
     const int n_terms = (need_prev ? k : 0) + (need_next ? k : 0);
@@ -463,6 +472,7 @@ adafuse_status adafuse_forward_merged(adafuse_ctx *ctx, const void *x, float *y,
 {
     if (!ctx || !x || !y) return ADAFUSE_ERR_NULL;
     if (!aligned16(x)) return ADAFUSE_ERR_ALIGN;
+    if (!on_ctx_device(ctx)) return ADAFUSE_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const uint16_t *xp = static_cast<const uint16_t *>(x);
     for (const adafuse_matrix_desc &m : ctx->mats) {
@@ -483,6 +493,7 @@ adafuse_status adafuse_forward_dynamic(adafuse_ctx *ctx, const int32_t *idx_host
         if (idx_host[j] < 0 || idx_host[j] >= ctx->E) return ADAFUSE_ERR_ARG;
     if (ctx->inplace) return ADAFUSE_ERR_ARG;  // needs the unmodified base weights
     if (!aligned16(x)) return ADAFUSE_ERR_ALIGN;
+    if (!on_ctx_device(ctx)) return ADAFUSE_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const uint16_t *xp = static_cast<const uint16_t *>(x);
     const int r = ctx->r;

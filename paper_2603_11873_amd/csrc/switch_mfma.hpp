@@ -61,7 +61,7 @@ template <int R, int NT, class S>
 __global__ __launch_bounds__(256) void switch_mfma_kernel(SwitchParams p)
 {
     constexpr int CH = R / 4;  // 4-wide chunks of the rank
-    constexpr int TR = S::TR, TC = S::TC, WR = S::WR, WC = S::WC, NGW = S::NGW, DW = S::DW;
+    constexpr int TR = S::TR, WR = S::WR, WC = S::WC, NGW = S::NGW, DW = S::DW;
     static_assert(R % 4 == 0 && NT >= 1 && NT <= kMaxTerms, "unsupported shape");
 
     __shared__ __align__(16) MfmaLds<R, NT, S> lds;
