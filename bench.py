@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--forward", action="store_true",
                     help="also time the step after the switch: merged GEMVs vs the un-merged dynamic-adapter path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-copy-ceiling", action="store_true",
+                    help="skip the plain-copy launches after the timed loop (for counter runs that average over dispatches)")
     ap.add_argument("--cpu-layers", type=int, default=2, help="layers of the model the oracle is timed on")
     return ap.parse_args()
 
@@ -100,6 +102,20 @@ def forward_context(torch, af, ctx, wl, mats, idx, gates, stream, reps=20):
     res["launches"] = {"merged_gemv": wl.n_mats, "dynamic_adapter": wl.n_mats * (1 + 2 * wl.k)}
     res["note"] = "one GEMV per matrix; the dynamic form adds a down- and an up-projection launch per selected expert"
     return res
+
+
+def timed_launches(torch, stream, fn, reps, warm=3):
+    """Mean and median us of one enqueue of fn on stream, from an event pair around each."""
+    for _ in range(warm):
+        fn()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in evs:
+        a.record(stream)
+        fn()
+        b.record(stream)
+    torch.cuda.synchronize()
+    us = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+    return {"mean": sum(us) / len(us), "median": us[len(us) // 2]}
 
 
 def main():
@@ -198,8 +214,33 @@ def main():
                      "kernel_us": {"mean": avg_kernel_s * 1e6, "median": srt[len(srt) // 2] * 1e3,
                                    "p95": srt[int(0.95 * (len(srt) - 1))] * 1e3, "min": srt[0] * 1e3}},
     }
+    with torch.cuda.stream(stream):
+        # the router alone, one token per launch (launch-latency bound: us only)
+        out["pregate_us"] = timed_launches(
+            torch, stream, lambda: af.pregate(hidden[0:1], router, wl.k, out=(idx[0:1], gates[0:1], None), stream=stream), 64)
+    if wl.repeat_prob > 0 and mode == af.SWAP:
+        # tokens that keep the previous token's expert set (fresh gates) vs tokens that change it
+        hidx = idx.cpu().tolist()
+        cls = {"same_set": [], "new_set": []}
+        for i, ms in enumerate(kernel_ms):
+            t = (args.warmup + i) % T
+            same = sorted(hidx[t]) == sorted(hidx[(t - 1) % T])
+            cls["same_set" if same else "new_set"].append(ms * 1e3)
+        out["roofline"]["kernel_us_by_token"] = {
+            k: {"tokens": len(v), "mean": sum(v) / len(v) if v else None} for k, v in cls.items()}
     if args.forward and not args.inplace:
         out["decode_context"] = forward_context(torch, af, ctx, wl, mats, idx, gates, stream)
+    if mode == af.SWAP and not args.inplace and not args.per_matrix and not args.no_copy_ceiling:
+        # practical ceiling: the plain 128-bit copy W_base -> W_work over the same tile table
+        with torch.cuda.stream(stream):
+            cp = timed_launches(torch, stream, lambda: ctx.fused_switch(None, None, None, None, wl.k, wl.scale,
+                                                                        af.UNMERGE, stream=stream), 16)
+            last = (args.warmup + args.steps - 1) % T   # leave W_work as the timed loop left it
+            ctx.fused_switch(None, None, idx[last], gates[last], wl.k, wl.scale, af.MERGE, stream=stream)
+            torch.cuda.synchronize()
+        copy_gbs = 4 * wl.elements / (cp["mean"] * 1e-6) / 1e9
+        out["roofline"]["copy_kernel"] = {"us": cp["mean"], "GB/s": copy_gbs, "frac_of_peak": copy_gbs / HBM_PEAK_GBS,
+                                          "switch_vs_copy": achieved / copy_gbs}
     if not args.no_cpu_baseline:
         t = (args.warmup + args.steps - 1) % T
         out["cpu_baseline"] = cpu_baseline(wl, mats, hidden, router, t, min(args.cpu_layers, wl.layers))

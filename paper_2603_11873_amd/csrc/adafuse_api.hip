@@ -26,7 +26,7 @@ struct adafuse_ctx {
     int32_t mfma_shape = 0;  // index into the matrix-core kernel's tile shapes
     int32_t gemm_waves = 4;  // waves per workgroup of the rank-looped kernel: tile 64 x (64 waves)
     bool inplace = false;    // every matrix has w_work == w_base
-    int32_t order = 512;     // tiles per XCD run (ADAFUSE_ORDER; 0 = plain order, 1 = an eighth of the list)
+    int32_t order = 1;       // tiles per XCD run (ADAFUSE_ORDER; 0 = plain order, 1 = an eighth of the list)
     int64_t n_tiles = 0, elements = 0;
     int device = -1;
     MatDev *d_mats = nullptr;
@@ -287,10 +287,10 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
     const size_t n = ht.size();
     ht.insert(ht.end(), ht.begin(), ht.begin() + n);
     if (c->order >= 1) {
-        const size_t G = c->order == 1 ? (n + 7) / 8 : (size_t)c->order;
-        deal_to_xcds(ht, 0, n, G);
+        auto run = [&](size_t count) { return c->order == 1 ? (count + 7) / 8 : (size_t)c->order; };
+        deal_to_xcds(ht, 0, n, run(n));
         for (size_t i = 0; i + 1 < mat_off.size(); ++i)
-            deal_to_xcds(ht, n + mat_off[i], n + mat_off[i + 1], G);
+            deal_to_xcds(ht, n + mat_off[i], n + mat_off[i + 1], run((size_t)(mat_off[i + 1] - mat_off[i])));
     }
 
     if (hipGetDevice(&c->device) != hipSuccess) return ADAFUSE_ERR_HIP;

@@ -126,6 +126,25 @@ __device__ __forceinline__ bool load_terms(const SwitchParams &p, Terms &t)
         t.e[j] = e < 0 ? 0 : (e >= p.E ? p.E - 1 : e);
         t.c[j] = c;
     }
+    // In place, an expert that both tokens selected enters once, with the difference
+    // of its two coefficients (zero when the gates are equal too: the kernels skip
+    // such terms), so the contraction covers only what changes between the tokens.
+    // Indices are compile-time constants after unrolling: the list stays in registers.
+    if (n_prev > 0 && n_next > 0) {
+#pragma unroll
+        for (int a = 0; a < NT; ++a) {
+            bool folded = false;
+#pragma unroll
+            for (int b = 0; b < NT; ++b) {
+                const bool hit = !folded && a < n_prev && b >= n_prev && b < n_prev + n_next && t.e[a] == t.e[b];
+                if (hit) {
+                    t.c[b] += t.c[a];
+                    t.c[a] = 0.0f;
+                    folded = true;
+                }
+            }
+        }
+    }
     return true;
 }
 

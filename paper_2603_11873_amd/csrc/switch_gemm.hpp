@@ -255,7 +255,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
 
     // ---- epilogue: each lane updates its pieces of the W tile in LDS, in the result
     // layout (column p of a group is accumulator cb = p&1, v = 4b + p/2); tile back out.
-    if (nt > 0) {  // nothing selected (un-merge out of place): the bits pass through untouched
+    if (c_last != 0.0f) {  // no term, or only zero coefficients: the bits pass through untouched (-0.0 stays -0.0)
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -500,7 +500,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams 
 
     // ---- epilogue: each lane updates its pieces of the W tile in LDS, in the result
     // layout (column p of a group is accumulator cb = p&1, v = 4b + p/2); tile back out.
-    if (nt > 0) {  // nothing selected (un-merge out of place): the bits pass through untouched
+    if (c_last != 0.0f) {  // no term, or only zero coefficients: the bits pass through untouched (-0.0 stays -0.0)
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll

@@ -373,6 +373,36 @@ def test_inplace_steps_match_oracle(oracle, kernel):
     ctx.close()
 
 
+@pytest.mark.parametrize("kernel", ALL_KERNELS)
+def test_inplace_experts_common_to_both_tokens(oracle, kernel):
+    """Hand-made transitions in which the two tokens share experts: one shared with different
+    gates, the same set with different gates, and the same set listed in the other order with
+    equal gates (the update is exactly zero, so the bits must not move)."""
+    wl = wlmod.WORKLOADS["toy"]
+    mats, base, ctx = _inplace_model(wl)
+    ctx.set_kernel(kernel)
+    dev = mats[0][0].device
+    host = [(wlmod.bits(wb), wlmod.bits(m[2]), wlmod.bits(m[3])) for wb, m in zip(base, mats)]
+    cases = [(([0, 2], [0.625, 0.375]), ([2, 3], [0.71875, 0.28125]), False),
+             (([0, 1], [0.59375, 0.40625]), ([0, 1], [0.5, 0.5]), False),
+             (([1, 3], [0.5625, 0.4375]), ([3, 1], [0.4375, 0.5625]), True)]
+    for (pi, pg), (ni, ng), frozen in cases:
+        prev = (np.asarray(pi, np.int32), np.asarray(pg, np.float32))
+        nxt = (np.asarray(ni, np.int32), np.asarray(ng, np.float32))
+        before = [oracle.merge(w, a, b, prev[0], prev[1], wl.scale) for w, a, b in host]
+        for m, bf in zip(mats, before):
+            m[1].copy_(wlmod.from_bits(bf))
+        ctx.fused_switch(torch.as_tensor(prev[0], device=dev), torch.as_tensor(prev[1], device=dev),
+                         torch.as_tensor(nxt[0], device=dev), torch.as_tensor(nxt[1], device=dev),
+                         wl.k, wl.scale, af.SWAP)
+        _sync()
+        for mat, bf in zip(mats, before):
+            _check_inplace_step(oracle, bf, mat, prev, nxt, wl.scale)
+            if frozen:
+                assert np.array_equal(wlmod.bits(mat[1]), bf)
+    ctx.close()
+
+
 def test_inplace_sequence_drifts_from_the_stateless_result(oracle):
     """Run the whole toy sequence in place on the GPU and measure how far the weights have
     wandered from the drift-free definition W_base + dW(last token) (oracle, from base)."""
