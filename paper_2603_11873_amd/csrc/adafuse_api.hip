@@ -136,6 +136,14 @@ bool launch_gemm_rw(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t 
     case 1: hipLaunchKernelGGL((switch_gemm_kernel<R, 1, NW>), grid, block, 0, s, p); return true;
     case 2: hipLaunchKernelGGL((switch_gemm_kernel<R, 2, NW>), grid, block, 0, s, p); return true;
     case 4:
+        if constexpr (R <= 16) {  // all four row operands fit beside the W tile: unrolled, no barrier in the contraction
+            static const bool looped = [] { const char *e = std::getenv("ADAFUSE_GEMM_FORM"); return e && std::atoi(e) == 2; }();
+            if (!looped) {
+                hipLaunchKernelGGL((switch_gemm_kernel<R, 4, NW>), grid, block, 0, s, p);
+                return true;
+            }
+        }
+        [[fallthrough]];
     case 8: hipLaunchKernelGGL((switch_gemm_loop_kernel<R, NW>), grid, block, 0, s, p); return true;
     default: return false;
     }

@@ -74,6 +74,28 @@ __device__ __forceinline__ void st_global_nt(T v, T *p)
     __builtin_nontemporal_store(v, (ADAFUSE_GLOBAL T *)p);
 }
 
+// Raw buffer addressing: a uniform descriptor (base and size in scalar registers), a
+// 32-bit byte offset per lane and a uniform byte offset per instruction, so a
+// group of loads that differ only in the uniform part shares ONE address
+// register.  Reads beyond `bytes` return zero.  Word 3 selects a 32-bit data
+// format (ignored by untyped loads, but a descriptor must name a valid one).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_buffer(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ uint32_t ld_buffer_b32(__amdgpu_buffer_rsrc_t rsrc, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)lane_off, (int)uniform_off, 0);
+}
+__device__ __forceinline__ uint2_t ld_buffer_b64(__amdgpu_buffer_rsrc_t rsrc, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_bit_cast(uint2_t, __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)lane_off, (int)uniform_off, 0));
+}
+__device__ __forceinline__ uint4_t ld_buffer_b128(__amdgpu_buffer_rsrc_t rsrc, uint32_t lane_off, uint32_t uniform_off)
+{
+    return __builtin_bit_cast(uint4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)lane_off, (int)uniform_off, 0));
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }

@@ -47,6 +47,17 @@ typedef __attribute__((ext_vector_type(16))) float float16_t;
 constexpr int kGemmTileRows = 64;
 constexpr int kGemmWaveCols = 64;  // a workgroup of NW waves covers 64 NW columns
 
+// The W tile in LDS: TR rows of TC bf16 with no padding (32 KB for 64 x 256, which
+// leaves 8 KB of a 40 KB share -- four workgroups per CU -- for the operands).  The
+// 16-byte pieces of a row are permuted by the row number instead: row-contiguous
+// accesses (in and out) stay conflict-free, and the result-layout accesses (one
+// piece column over 32 rows) spread over all banks as they would with a padded pitch.
+template <int TC>
+__device__ __forceinline__ uint4_t *w_slot(uint16_t (*s_w)[TC], int row, int piece)
+{
+    return reinterpret_cast<uint4_t *>(&s_w[row][8 * (piece ^ (row & 31))]);
+}
+
 template <int R, int NT>
 struct GemmPlan {
     static constexpr int KS = (R + 15) / 16;          // k-steps (16 rank indices) per expert
@@ -57,8 +68,10 @@ struct GemmPlan {
     static constexpr int QMAX = KCH == 1 ? 8 : 4;     // chunks in flight: at most 64 VGPRs
     static constexpr int QX = TOT < QMAX ? TOT : QMAX;
     static constexpr int RP = R < 8 ? 8 : R;          // rank padded to one 16-byte piece
-    static constexpr int BP = (R < 16 ? 16 : R) + 8;  // LDS row pitch of a staged B slice (bf16), 16-byte pad
-    static constexpr int BMAX = 2;                    // B slices resident in LDS (more cost a workgroup per CU)
+    // LDS row pitch of a staged B slice (bf16).  One k-step per row (32 bytes) needs no
+    // pad: a wave's 64 reads of 16 bytes cover 1 KB contiguously.  Longer rows get 16 bytes.
+    static constexpr int BP = R <= 16 ? 16 : R + 8;
+    static constexpr int BMAX = R <= 16 ? 4 : 2;      // B slices resident in LDS (more cost a workgroup per CU)
     static constexpr int NB = NT < BMAX ? NT : BMAX;  // B slices resident
     static constexpr int BV = kGemmTileRows * RP / 8;  // 16-byte pieces of one expert's B slice
     static constexpr int BQ(int nthr) { return (BV + nthr - 1) / nthr; }  // ... per thread
@@ -75,11 +88,10 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
     constexpr int RP = P::RP, BP = P::BP, BV = P::BV, BQ = P::BQ(NTHR);
     constexpr bool kPadded = P::kPadded;
     constexpr int TR = kGemmTileRows, TC = kGemmWaveCols * NW;
-    constexpr int WP = TC + 8;              // LDS row pitch of the W tile (bf16)
     constexpr int WQ = TR * TC / 8 / NTHR;  // 16-byte pieces of the W tile per thread
 
     __shared__ __align__(16) uint16_t s_b[NB][TR][BP];  // row operands of the resident experts
-    __shared__ __align__(16) uint16_t s_w[TR][WP];      // the W tile, on its way in and out
+    __shared__ __align__(16) uint16_t s_w[TR][TC];      // the W tile, on its way in and out (pieces permuted: w_slot)
 
     Terms terms;
     if (!load_terms<NT>(p, terms)) return;
@@ -96,19 +108,33 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
     const int rows_left = tile.rows_left, cols_left = tile.cols_left;
     const int ldw = tile.ldw;
 
-    // ---- request everything, in the order of use
+    // ---- request everything.  Loads return in issue order, so operand loads (cache
+    // hits) queued behind the W loads (HBM) sit on their return slots until W has
+    // landed.  With one or two experts that costs nothing and W should go first;
+    // with four experts' operands in the queue it slowed the W loads themselves
+    // (measured: 5.8 ms against 4.7 ms per launch on the 8B shape), so there the
+    // operands go first and W last.
+    constexpr bool kOperandsFirst = NT >= 4;
     uint4_t wreg[WQ];
+    auto request_w = [&]() {
 #pragma unroll
-    for (int i = 0; i < WQ; ++i) {
-        const int q = tid + NTHR * i;
-        const int row = q / (TC / 8), pc = q % (TC / 8);
-        const int cr = row < rows_left ? row : rows_left - 1;
-        const int cc = 8 * pc < cols_left ? 8 * pc : cols_left - 8;
-        wreg[i] = ld_global_nt(reinterpret_cast<const uint4_t *>(tile.w_src + (size_t)cr * ldw + cc));
-    }
+        for (int i = 0; i < WQ; ++i) {
+            const int q = tid + NTHR * i;
+            const int row = q / (TC / 8), pc = q % (TC / 8);
+            const int cr = row < rows_left ? row : rows_left - 1;
+            const int cc = 8 * pc < cols_left ? 8 * pc : cols_left - 8;
+            wreg[i] = ld_global_nt(reinterpret_cast<const uint4_t *>(tile.w_src + (size_t)cr * ldw + cc));
+        }
+    };
+    if constexpr (!kOperandsFirst) request_w();
 
+    // Operand loads go through buffer descriptors: base and size of one expert's
+    // slice in scalar registers, ONE 32-bit offset register per lane for all loads
+    // of a group, the rest of the address uniform.  (Shapes are limited to 2^22
+    // in either direction: a slice stays below 2^31 bytes.)
+    const uint32_t b_bytes = (uint32_t)(m.out - tile.row0) * R * 2u;  // from the tile's first row to the end of the expert
     auto fetch_b = [&](uint4_t (&v)[BQ], int e) {
-        const uint16_t *bsrc = m.b_bank + ((size_t)e * m.out + tile.row0) * R;
+        const __amdgpu_buffer_rsrc_t rs = make_buffer(m.b_bank + ((size_t)e * m.out + tile.row0) * R, b_bytes);
 #pragma unroll
         for (int i = 0; i < BQ; ++i) {
             const int q = tid + NTHR * i;
@@ -116,9 +142,9 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
             const int cr = row < rows_left ? row : rows_left - 1;
             if (q < BV) {
                 if constexpr (R >= 8) {
-                    v[i] = ld_global(reinterpret_cast<const uint4_t *>(bsrc + (size_t)cr * R + 8 * piece));
+                    v[i] = ld_buffer_b128(rs, 2u * ((uint32_t)cr * R + 8u * piece), 0u);
                 } else {  // rank 4: a row is 8 bytes
-                    const uint2_t t = ld_global(reinterpret_cast<const uint2_t *>(bsrc + (size_t)cr * R));
+                    const uint2_t t = ld_buffer_b64(rs, 2u * (uint32_t)cr * R, 0u);
                     v[i] = uint4_t{t[0], t[1], 0u, 0u};
                 }
             }
@@ -143,24 +169,18 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
     struct XChunk {
         uint32_t d[KCH][8];
     };
+    const uint32_t in_bytes = 2u * (uint32_t)m.in;
+    const uint32_t xoff = 8u * h * in_bytes + 2u * (uint32_t)acol;  // rank index 8h of a k-step, this lane's columns
     auto fetch_x = [&](XChunk &x, int e, int kc) {
-        if constexpr (kPadded) {
-            // rank indices 8h + i beyond R are zero: read a clamped index, then clear
-            const uint16_t *abase = m.a_bank + (size_t)e * R * m.in + acol;
+        const __amdgpu_buffer_rsrc_t rs = make_buffer(m.a_bank + (size_t)e * R * m.in, (uint32_t)R * in_bytes);
+#pragma unroll
+        for (int s2 = 0; s2 < KCH; ++s2)
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int kap = 8 * h + i;
-                const uint32_t v = ld_global(reinterpret_cast<const uint32_t *>(abase + (size_t)(kap < R ? kap : R - 1) * m.in));
-                x.d[0][i] = kap < R ? v : 0u;
+                // rank index 16 (KCH kc + s2) + 8h + i; beyond a padded rank the read is outside the slice (zero) and cleared
+                const uint32_t v = ld_buffer_b32(rs, xoff, (uint32_t)(16 * (KCH * kc + s2) + i) * in_bytes);
+                x.d[s2][i] = (kPadded && 8 * h + i >= R) ? 0u : v;
             }
-        } else {
-            const uint16_t *abase = m.a_bank + ((size_t)e * R + 16 * KCH * kc + 8 * h) * m.in + acol;
-#pragma unroll
-            for (int s2 = 0; s2 < KCH; ++s2)
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    x.d[s2][i] = ld_global(reinterpret_cast<const uint32_t *>(abase + (size_t)(16 * s2 + i) * m.in));
-        }
     };
 
     uint4_t vb[NB][BQ];
@@ -171,16 +191,24 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
 #pragma unroll
     for (int i = 0; i < QX; ++i)
         if (i / NCH < nt) fetch_x(xq[i], terms.e[i / NCH], i % NCH);
+    if constexpr (kOperandsFirst) {
+        request_w();
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            if (j < nt) stash_b(vb[j], j);
+    }
 
     // W tile and row operands into LDS as they land: the registers are free for the contraction
 #pragma unroll
     for (int i = 0; i < WQ; ++i) {
         const int q = tid + NTHR * i;
-        *reinterpret_cast<uint4_t *>(&s_w[q / (TC / 8)][8 * (q % (TC / 8))]) = wreg[i];
+        *w_slot<TC>(s_w, q / (TC / 8), q % (TC / 8)) = wreg[i];
     }
+    if constexpr (!kOperandsFirst) {
 #pragma unroll
-    for (int j = 0; j < NB; ++j)
-        if (j < nt) stash_b(vb[j], j);
+        for (int j = 0; j < NB; ++j)
+            if (j < nt) stash_b(vb[j], j);
+    }
     __syncthreads();
 
     float16_t acc[2][2];
@@ -260,7 +288,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                uint4_t *slot = reinterpret_cast<uint4_t *>(&s_w[32 * rb + n][lcol0 + 16 * b + 8 * h]);
+                uint4_t *slot = w_slot<TC>(s_w, 32 * rb + n, lcol0 / 8 + 2 * b + h);
                 const uint4_t wv = *slot;
                 float o[8];
 #pragma unroll
@@ -278,7 +306,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
         const int q = tid + NTHR * i;
         const int row = q / (TC / 8), pc = q % (TC / 8);
         if (row < rows_left && 8 * pc < cols_left)
-            st_global_nt(*reinterpret_cast<const uint4_t *>(&s_w[row][8 * pc]),
+            st_global_nt(*w_slot<TC>(s_w, row, pc),
                          reinterpret_cast<uint4_t *>(tile.w_dst + (size_t)row * ldw + 8 * pc));
     }
 }
@@ -297,18 +325,17 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams 
     constexpr bool kPadded = R < 16;    // one k-step whose rank indices >= R are zero
     constexpr int TR = kGemmTileRows;   // tile rows
     constexpr int RP = R < 8 ? 8 : R;   // rank padded to one 16-byte piece
-    constexpr int BP = (R < 16 ? 16 : R) + 8;  // LDS row pitch of the staged B slice (bf16): 16-byte pad against bank conflicts
+    constexpr int BP = R <= 16 ? 16 : R + 8;  // LDS row pitch of the staged B slice (bf16): a 16-byte pad once a row is longer than a k-step
     constexpr int BV = TR * RP / 8;     // 16-byte pieces of one expert's B slice for the tile
     constexpr int BQ = (BV + 64 * NW - 1) / (64 * NW);  // ... per thread
     constexpr int NTHR = 64 * NW;
     constexpr int TC = kGemmWaveCols * NW;  // tile columns
-    constexpr int WP = TC + 8;          // LDS row pitch of the W tile (bf16)
     constexpr int WQ = TR * TC / 8 / (64 * NW);  // 16-byte pieces of the W tile per thread
 
     __shared__ int32_t s_e[kMaxTerms];
     __shared__ float s_c[kMaxTerms];
     __shared__ __align__(16) uint16_t s_b[2][TR][BP];  // row operand of the current / next expert
-    __shared__ __align__(16) uint16_t s_w[TR][WP];     // the W tile, on its way in and out
+    __shared__ __align__(16) uint16_t s_w[TR][TC];     // the W tile, on its way in and out (pieces permuted: w_slot)
     {
         Terms terms;
         if (!load_terms<kMaxTerms>(p, terms)) return;
@@ -368,8 +395,10 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams 
     // The row operand of one expert for the whole tile -- TR rows x R, contiguous in
     // the B bank -- is fetched by the workgroup in 16-byte pieces (fully coalesced)
     // and kept in LDS; rows beyond the edge repeat the last row.
+    // (operand loads through buffer descriptors, as in the kernel above)
+    const uint32_t b_bytes = (uint32_t)(m.out - tile.row0) * R * 2u;
     auto fetch_b = [&](uint4_t (&v)[BQ], int e) {
-        const uint16_t *bsrc = m.b_bank + ((size_t)e * m.out + tile.row0) * R;
+        const __amdgpu_buffer_rsrc_t rs = make_buffer(m.b_bank + ((size_t)e * m.out + tile.row0) * R, b_bytes);
 #pragma unroll
         for (int i = 0; i < BQ; ++i) {
             const int q = tid + NTHR * i;
@@ -377,9 +406,9 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams 
             const int cr = row < rows_left ? row : rows_left - 1;
             if (q < BV) {
                 if constexpr (R >= 8) {
-                    v[i] = ld_global(reinterpret_cast<const uint4_t *>(bsrc + (size_t)cr * R + 8 * piece));
+                    v[i] = ld_buffer_b128(rs, 2u * ((uint32_t)cr * R + 8u * piece), 0u);
                 } else {  // rank 4: a row is 8 bytes
-                    const uint2_t t = ld_global(reinterpret_cast<const uint2_t *>(bsrc + (size_t)cr * R));
+                    const uint2_t t = ld_buffer_b64(rs, 2u * (uint32_t)cr * R, 0u);
                     v[i] = uint4_t{t[0], t[1], 0u, 0u};
                 }
             }
@@ -403,24 +432,17 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams 
     struct XChunk {
         uint32_t d[KCH][8];
     };
+    const uint32_t in_bytes = 2u * (uint32_t)m.in;
+    const uint32_t xoff = 8u * h * in_bytes + 2u * (uint32_t)acol;  // rank index 8h of a k-step, this lane's columns
     auto fetch_x = [&](XChunk &x, int e, int kc) {
-        if constexpr (kPadded) {
-            // rank indices 8h + i beyond R are zero: read a clamped index, then clear
-            const uint16_t *abase = m.a_bank + (size_t)e * R * m.in + acol;
+        const __amdgpu_buffer_rsrc_t rs = make_buffer(m.a_bank + (size_t)e * R * m.in, (uint32_t)R * in_bytes);
+#pragma unroll
+        for (int s2 = 0; s2 < KCH; ++s2)
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int kap = 8 * h + i;
-                const uint32_t v = ld_global(reinterpret_cast<const uint32_t *>(abase + (size_t)(kap < R ? kap : R - 1) * m.in));
-                x.d[0][i] = kap < R ? v : 0u;
+                const uint32_t v = ld_buffer_b32(rs, xoff, (uint32_t)(16 * (KCH * kc + s2) + i) * in_bytes);
+                x.d[s2][i] = (kPadded && 8 * h + i >= R) ? 0u : v;
             }
-        } else {
-            const uint16_t *abase = m.a_bank + ((size_t)e * R + 16 * KCH * kc + 8 * h) * m.in + acol;
-#pragma unroll
-            for (int s2 = 0; s2 < KCH; ++s2)
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    x.d[s2][i] = ld_global(reinterpret_cast<const uint32_t *>(abase + (size_t)(16 * s2 + i) * m.in));
-        }
     };
     auto term_coeff = [&](int j) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(s_c[j]))); };
     auto term_expert = [&](int j) { return __builtin_amdgcn_readfirstlane(s_e[j]); };
@@ -445,7 +467,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams 
 #pragma unroll
     for (int i = 0; i < WQ; ++i) {
         const int q = tid + NTHR * i;
-        *reinterpret_cast<uint4_t *>(&s_w[q / (TC / 8)][8 * (q % (TC / 8))]) = wreg[i];
+        *w_slot<TC>(s_w, q / (TC / 8), q % (TC / 8)) = wreg[i];
     }
     if (j < nt) stash_b(vb, 0);
     __syncthreads();
@@ -505,7 +527,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams 
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                uint4_t *slot = reinterpret_cast<uint4_t *>(&s_w[lrow0 + 32 * rb + n][lcol0 + 16 * b + 8 * h]);
+                uint4_t *slot = w_slot<TC>(s_w, lrow0 + 32 * rb + n, lcol0 / 8 + 2 * b + h);
                 const uint4_t wv = *slot;
                 float o[8];
 #pragma unroll
@@ -523,7 +545,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams 
         const int q = tid + NTHR * i;
         const int row = q / (TC / 8), pc = q % (TC / 8);
         if (row < rows_left && 8 * pc < cols_left)
-            st_global_nt(*reinterpret_cast<const uint4_t *>(&s_w[row][8 * pc]),
+            st_global_nt(*w_slot<TC>(s_w, row, pc),
                          reinterpret_cast<uint4_t *>(tile.w_dst + (size_t)row * ldw + 8 * pc));
     }
 }
