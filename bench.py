@@ -181,6 +181,19 @@ def main():
 
     ms_per_step = wall * 1e3 / args.steps
     kernel_ms = [a.elapsed_time(b) for a, b in events]           # the switch launch alone
+    # A SWAP whose previous decision is bit-identical to the next returns at once (nothing to do):
+    # such launches stay in `value` (they are part of the sequence) but never enter the rate.
+    early_outs = 0
+    if mode == af.SWAP:
+        hi, hg = idx.cpu(), gates.cpu().view(torch.int32)
+        keep = []
+        for i, ms in enumerate(kernel_ms):
+            cur, prv = (args.warmup + i) % T, (args.warmup + i - 1) % T
+            if torch.equal(hi[cur], hi[prv]) and torch.equal(hg[cur], hg[prv]):
+                early_outs += 1
+            else:
+                keep.append(ms)
+        kernel_ms_all, kernel_ms = kernel_ms, (keep or kernel_ms)
     avg_kernel_s = sum(kernel_ms) / len(kernel_ms) * 1e-3
     alg_bytes = wl.algorithmic_bytes if mode == af.SWAP else 4 * wl.elements
     if args.inplace:   # the previous token's slices are read too
@@ -210,7 +223,7 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": read_traffic(wl.name, kernel_name) if mode == af.SWAP and not args.inplace else None,
                      "kernel": f"switch_{kernel_name}_kernel" if mode == af.SWAP else "switch_copy_kernel",
-                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "algorithmic_bytes_per_launch": alg_bytes, "early_out_launches_excluded": early_outs,
                      "kernel_us": {"mean": avg_kernel_s * 1e6, "median": srt[len(srt) // 2] * 1e3,
                                    "p95": srt[int(0.95 * (len(srt) - 1))] * 1e3, "min": srt[0] * 1e3}},
     }
@@ -222,7 +235,7 @@ def main():
         # tokens that keep the previous token's expert set (fresh gates) vs tokens that change it
         hidx = idx.cpu().tolist()
         cls = {"same_set": [], "new_set": []}
-        for i, ms in enumerate(kernel_ms):
+        for i, ms in enumerate(kernel_ms_all):
             t = (args.warmup + i) % T
             same = sorted(hidx[t]) == sorted(hidx[(t - 1) % T])
             cls["same_set" if same else "new_set"].append(ms * 1e3)

@@ -132,14 +132,20 @@ template <int R, int NW>
 bool launch_gemm_rw(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t s)
 {
     const dim3 grid((unsigned)n_tiles), block(64 * NW);
+    // ADAFUSE_GEMM_FORM=2 keeps the run-time expert loop for every launch with 4 terms (a measurement knob)
+    static const bool looped = [] { const char *e = std::getenv("ADAFUSE_GEMM_FORM"); return e && std::atoi(e) == 2; }();
     switch (nt) {
     case 1: hipLaunchKernelGGL((switch_gemm_kernel<R, 1, NW>), grid, block, 0, s, p); return true;
     case 2: hipLaunchKernelGGL((switch_gemm_kernel<R, 2, NW>), grid, block, 0, s, p); return true;
     case 4:
         if constexpr (R <= 16) {  // all four row operands fit beside the W tile: unrolled, no barrier in the contraction
-            static const bool looped = [] { const char *e = std::getenv("ADAFUSE_GEMM_FORM"); return e && std::atoi(e) == 2; }();
             if (!looped) {
                 hipLaunchKernelGGL((switch_gemm_kernel<R, 4, NW>), grid, block, 0, s, p);
+                return true;
+            }
+        } else if constexpr (R <= 64) {  // 8 or 16 k-steps through the ring of row-operand pieces
+            if (!looped) {
+                hipLaunchKernelGGL((switch_gemm_ring_kernel<R, 4, NW>), grid, block, 0, s, p);
                 return true;
             }
         }

@@ -1,5 +1,6 @@
 // Device-side tables and small bf16 helpers shared by the switch and router kernels.
 #pragma once
+#include <type_traits>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
