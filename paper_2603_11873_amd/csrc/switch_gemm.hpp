@@ -25,13 +25,21 @@
 //   * Result layout with that column assignment: a lane holds, per row block and
 //     b = 0..3, the 8 contiguous columns base + 16 b + 8 (lane/32) + 0..7 of row
 //     lane%32 -- one 16-byte piece of the W tile each.
-// Everything the tile needs is requested at the start, in the order it is used
-// (loads return in issue order): W, row operands, the first column operands.
-// All loads are unconditional with clamped addresses: a row or column beyond the
-// matrix edge only feeds results that are never stored, and loads inside
-// branches would each get their own wait.
-// Two forms: switch_gemm_kernel<R, NT> for 1 or 2 terms (the usual top-2, out of
-// place), fully unrolled; switch_gemm_loop_kernel<R> for more.
+// Everything the tile needs is requested at the start (loads return in issue
+// order): W, row operands, the first column operands -- or, with four experts'
+// operands to queue, the operands first and W last.  All loads are unconditional
+// with clamped addresses: a row or column beyond the matrix edge only feeds
+// results that are never stored, and loads inside branches make the compiler
+// fall back to waiting for every outstanding load.  Operand loads use buffer
+// descriptors (one address register per lane for a whole group of loads).
+// The W tile sits in LDS unpadded (32 KB), its 16-byte pieces permuted by the
+// row number (w_slot), which leaves 8 KB of a four-workgroups-per-CU share of
+// LDS for the row operands.
+// Three forms: switch_gemm_kernel<R, NT> for 1 or 2 terms at any rank and 4
+// terms up to rank 16, fully unrolled with every row operand resident;
+// switch_gemm_ring_kernel<R, 4> for 4 terms at ranks 32 and 64 (8 or 16
+// k-steps through a ring of 2 KB row-operand pieces); switch_gemm_loop_kernel<R>
+// for the rest (8 terms, or 4 at rank 128): a run-time loop over the experts.
 // Gates stay out of the bf16 operands.  Experts are chained in ONE accumulator:
 //   acc = P_0;  acc = acc * (c_0/c_1) + P_1;  ...;  W' = rn_bf16(W + c_last * acc)
 // which equals W + sum_j c_j P_j up to fp32 rounding of the ratios (terms with a
@@ -311,13 +319,17 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
     }
 }
 
-// The same contraction for ranks of 32 and more, where a whole B slice per expert
-// would cost workgroups per CU: the unit is ONE k-step (16 rank indices of one
-// expert), fully unrolled over all NT * R/16 of them.  The row operand of a k-step
-// is a 64 x 16 piece of 2 KB; four of them sit in a ring in LDS, the next BD are in
-// registers on their way, and a piece moves into the ring slot of the k-step that
-// has just been consumed (one barrier per k-step once the ring turns).  With the
-// unpadded W tile that is exactly 40 KB: four workgroups per CU at every rank.
+// The same contraction for long inner dimensions at ranks of 32 and more, where a
+// whole B slice per expert would cost workgroups per CU: the unit is ONE k-step
+// (16 rank indices of one expert), fully unrolled over all NT * R/16 of them.  The
+// row operand of a k-step is a 64 x 16 piece of 2 KB; four of them sit in a ring
+// in LDS, the next BD are in registers on their way, and a piece moves into the
+// ring slot of the k-step that has just been consumed (one barrier per k-step
+// once the ring turns).  With the unpadded W tile that is exactly 40 KB: four
+// workgroups per CU at every rank.  Used for 4 terms (in place with top-2, or
+// top-4), where it beats the run-time expert loop by 8 % (rank 32) to 27 % (rank
+// 64); with 1 or 2 terms the unrolled kernel above is faster (its contraction
+// has no barrier) and is used instead.
 template <int R, int NT, int NW>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(4, 4))) void switch_gemm_ring_kernel(SwitchParams p)
 {
