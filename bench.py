@@ -38,6 +38,9 @@ def parse_args():
                     help="the paper's 'simple merge' ablation: one launch per adapted matrix instead of one for all")
     ap.add_argument("--forward", action="store_true",
                     help="also time the step after the switch: merged GEMVs vs the un-merged dynamic-adapter path")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the whole token sequence (T x [pregate, switch]) in one HIP graph and replay it; "
+                         "for launch-bound workloads (toy).  Reported separately as graph_us_per_token")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-ceiling", action="store_true",
                     help="skip the plain-copy launches after the timed loop (for counter runs that average over dispatches)")
@@ -227,6 +230,21 @@ def main():
                      "kernel_us": {"mean": avg_kernel_s * 1e6, "median": srt[len(srt) // 2] * 1e3,
                                    "p95": srt[int(0.95 * (len(srt) - 1))] * 1e3, "min": srt[0] * 1e3}},
     }
+    if args.graph:
+        # the same T steps as one graph: no per-launch host cost between the kernels
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for t in range(T):
+                step(t)
+        replays = max(1, (args.steps + T - 1) // T)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        out["graph_us_per_token"] = {"value": (time.perf_counter() - t0) / (replays * T) * 1e6, "tokens_per_graph": T,
+                                     "replays": replays, "eager_us_per_token": ms_per_step * 1e3}
     with torch.cuda.stream(stream):
         # the router alone, one token per launch (launch-latency bound: us only)
         out["pregate_us"] = timed_launches(
