@@ -227,6 +227,48 @@ def test_ragged_shapes_and_padding(oracle, kernel, out, in_, ldw, E, r, k):
 
 
 @pytest.mark.parametrize("kernel", ALL_KERNELS)
+@pytest.mark.parametrize("r", [8, 32])
+def test_fewer_experts_than_the_context_allows(oracle, kernel, r):
+    """A context made for top-4 takes calls with k = 1..4 (each picks its own kernel instance),
+    and a bank with a single expert works."""
+    dev = torch.device("cuda:0")
+    g = torch.Generator().manual_seed(77 + r)
+    out, in_, E = 150, 280, 5
+    wb = (0.02 * torch.randn((out, in_), generator=g)).to(torch.bfloat16).to(dev)
+    ww = torch.empty_like(wb)
+    a = (in_ ** -0.5 * torch.randn((E, r, in_), generator=g)).to(torch.bfloat16).to(dev)
+    b = (0.05 * torch.randn((E, out, r), generator=g)).to(torch.bfloat16).to(dev)
+    ctx = af.Context([(wb, ww, a, b)], 4)
+    ctx.set_kernel(kernel)
+    tally = Tally()
+    for k in (1, 2, 3, 4, 2):
+        idx = torch.randperm(E, generator=g)[:k].to(torch.int32)
+        gates = torch.softmax(torch.randn(k, generator=g), 0)
+        ww.view(torch.int16).fill_(0x7FC1)
+        if kernel == af.KERNEL_VALU and k * r * 768 > 65536:
+            with pytest.raises(af.AdafuseError):   # more than the baseline kernel can stage in LDS: refused
+                ctx.fused_switch(None, None, idx.to(dev), gates.to(dev), k, 2.0, af.MERGE)
+            continue
+        ctx.fused_switch(None, None, idx.to(dev), gates.to(dev), k, 2.0, af.MERGE)
+        _sync()
+        tally.add(compare(oracle, wlmod.bits(wb), wlmod.bits(a), wlmod.bits(b), wlmod.bits(ww),
+                          idx.numpy(), gates.numpy(), 2.0), ULP_TOL, (kernel, r, k))
+    with pytest.raises(af.AdafuseError):
+        ctx.fused_switch(None, None, idx.to(dev), gates.to(dev), 5, 2.0, af.MERGE)   # more than the context's k_max
+    ctx.close()
+    one = af.Context([(wb, ww, a[:1].contiguous(), b[:1].contiguous())], 1)
+    one.set_kernel(kernel)
+    i1 = torch.zeros(1, dtype=torch.int32)
+    g1 = torch.ones(1)
+    one.fused_switch(None, None, i1.to(dev), g1.to(dev), 1, 2.0, af.MERGE)
+    _sync()
+    tally.add(compare(oracle, wlmod.bits(wb), wlmod.bits(a[:1]), wlmod.bits(b[:1]), wlmod.bits(ww), i1.numpy(), g1.numpy(), 2.0),
+              ULP_TOL, (kernel, r, "one expert"))
+    tally.finish(MAX_DIFF_FRACTION)
+    one.close()
+
+
+@pytest.mark.parametrize("kernel", ALL_KERNELS)
 def test_one_full_layer_of_the_7b_shape(oracle, kernel):
     """Every element of the seven matrices of one Llama-2-7B-shaped layer (several
     hundred tiles per matrix, 11008 is not a multiple of the tile height)."""
