@@ -44,7 +44,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-ceiling", action="store_true",
                     help="skip the plain-copy launches after the timed loop (for counter runs that average over dispatches)")
-    ap.add_argument("--cpu-layers", type=int, default=2, help="layers of the model the oracle is timed on")
+    ap.add_argument("--cpu-layers", type=int, default=16,
+                    help="layers of the model the oracle is timed on (16 of the 7B shape: about 10 s on 16 host threads)")
     return ap.parse_args()
 
 
