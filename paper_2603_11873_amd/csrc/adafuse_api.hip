@@ -149,8 +149,17 @@ bool launch_gemm_rw(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t 
                 return true;
             }
         }
-        [[fallthrough]];
-    case 8: hipLaunchKernelGGL((switch_gemm_loop_kernel<R, NW>), grid, block, 0, s, p); return true;
+        hipLaunchKernelGGL((switch_gemm_loop_kernel<R, NW>), grid, block, 0, s, p);
+        return true;
+    case 8:
+        if constexpr (R == 16) {  // 8 k-steps through the ring
+            if (!looped) {
+                hipLaunchKernelGGL((switch_gemm_ring_kernel<R, 8, NW>), grid, block, 0, s, p);
+                return true;
+            }
+        }
+        hipLaunchKernelGGL((switch_gemm_loop_kernel<R, NW>), grid, block, 0, s, p);
+        return true;
     default: return false;
     }
 }

@@ -37,9 +37,9 @@
 // LDS for the row operands.
 // Three forms: switch_gemm_kernel<R, NT> for 1 or 2 terms at any rank and 4
 // terms up to rank 16, fully unrolled with every row operand resident;
-// switch_gemm_ring_kernel<R, 4> for 4 terms at ranks 32 and 64 (8 or 16
-// k-steps through a ring of 2 KB row-operand pieces); switch_gemm_loop_kernel<R>
-// for the rest (8 terms, or 4 at rank 128): a run-time loop over the experts.
+// switch_gemm_ring_kernel<R, NT> for 4 terms at ranks 32 and 64 and 8 terms at
+// rank 16 (8 or 16 k-steps through a ring of 2 KB row-operand pieces);
+// switch_gemm_loop_kernel<R> for the rest: a run-time loop over the experts.
 // Gates stay out of the bf16 operands.  Experts are chained in ONE accumulator:
 //   acc = P_0;  acc = acc * (c_0/c_1) + P_1;  ...;  W' = rn_bf16(W + c_last * acc)
 // which equals W + sum_j c_j P_j up to fp32 rounding of the ratios (terms with a
@@ -333,7 +333,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
 template <int R, int NT, int NW>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(4, 4))) void switch_gemm_ring_kernel(SwitchParams p)
 {
-    static_assert(R % 16 == 0 && R >= 32, "ranks with two or more k-steps");
+    static_assert(R % 16 == 0, "whole k-steps");
     constexpr int KS = R / 16;          // k-steps per expert
     constexpr int STEPS = NT * KS;      // k-steps per tile
     constexpr int NS = 4;               // ring slots

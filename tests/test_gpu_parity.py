@@ -568,11 +568,11 @@ def test_per_matrix_launches_give_the_same_bits(oracle):
 
 @pytest.mark.parametrize("r,k,inplace", [(64, 2, False), (128, 2, False), (64, 2, True), (16, 4, False), (32, 1, True),
                                          (32, 4, False), (64, 4, False), (32, 2, True), (32, 3, False), (16, 3, False),
-                                         (16, 4, True), (8, 4, True), (128, 4, False), (64, 3, True)])
+                                         (16, 4, True), (8, 4, True), (128, 4, False), (64, 3, True), (16, 3, True)])
 def test_rank_looped_kernel_modes(oracle, r, k, inplace):
     """The rank-looped kernels in all their forms -- unrolled (1, 2 or 4 terms), the k-step ring
-    (4 terms at ranks 32 and 64, also with a term left unused: k = 3) and the run-time expert
-    loop (8 terms, or 4 at rank 128): MERGE / SWAP / UNMERGE, out of place and in place, two
+    (4 terms at ranks 32 and 64, 8 terms at rank 16, also with terms left unused: k = 3) and
+    the run-time expert loop (8 terms at other ranks, or 4 at rank 128): MERGE / SWAP / UNMERGE, out of place and in place, two
     ragged matrices."""
     dev = torch.device("cuda:0")
     g = torch.Generator().manual_seed(r * 10 + k)
