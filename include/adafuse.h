@@ -161,8 +161,12 @@ adafuse_status adafuse_pregate(const void *hidden, const void *w_router,
  *   MERGE   W <- rn_bf16(W + dW(next));  UNMERGE  W <- rn_bf16(W - dW(prev));
  *   SWAP    W <- rn_bf16(W - dW(prev) + dW(next)), the signed concatenation
  *           [-DOWN^{t-1}, DOWN^t] summed in fp32 and rounded once per call.
+ *   An expert listed in both prev and next enters once, with the difference of
+ *   its two coefficients (dropped when that is exactly zero).
  *   prev is required for UNMERGE and SWAP; a SWAP with prev bit-identical to next
  *   is an exactly-zero update and returns without touching W.
+ * Both entry points only enqueue kernels (no allocation, no memset, no
+ * synchronisation), so they may be recorded into a HIP graph.
  * Each W element is read once and written once (2 + 2 bytes); the selected A/B
  * slices are staged in registers and LDS.  Expert indices outside [0,E) in device memory are
  * clamped into range, not detected.  The call enqueues on `hip_stream` and
