@@ -305,7 +305,12 @@ def test_full_size_models_sampled_rows(oracle, name):
     assert np.array_equal(idx.cpu().numpy(), hidx)
     assert np.allclose(gates.cpu().numpy(), hg, rtol=1e-6, atol=0)
     rng = np.random.default_rng(wl.seed)
-    checkpoints = sorted({0, 1, wl.T // 2, wl.T - 1})
+    checkpoints = {0, 1, wl.T // 2, wl.T - 1}
+    if wl.repeat_prob > 0:   # the first token that keeps its predecessor's expert set (fresh gates)
+        first_repeat = next((t for t in range(1, wl.T) if sorted(hidx[t]) == sorted(hidx[t - 1])), None)
+        assert first_repeat is not None
+        checkpoints.add(first_repeat)
+    checkpoints = sorted(checkpoints)
     tally = Tally()
     m.ctx.fused_switch(None, None, idx[0], gates[0], wl.k, wl.scale, af.MERGE)
     for t in range(wl.T):
