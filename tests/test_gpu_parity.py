@@ -4,6 +4,8 @@ Tolerances (from the benchmark spec): merged weights within 1 bf16 ULP of the
 oracle's single-rounded value; fp32 router logits within 1e-5 relative; top-k
 indices bit-exact; gates within 1e-5 relative.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -327,6 +329,30 @@ def test_full_size_models_sampled_rows(oracle, name):
     # nothing left unwritten anywhere: no element still holds the NaN sentinel
     for _, ww, _, _ in m.mats[:: max(1, len(m.mats) // 16)]:
         assert not bool((ww.view(torch.int16) == 0x7FC1).any())
+    m.close()
+
+
+@pytest.mark.skipif(os.environ.get("ADAFUSE_FULL_CHECK") != "1",
+                    reason="minutes of oracle time per model: set ADAFUSE_FULL_CHECK=1 to run")
+@pytest.mark.parametrize("name", ["llama2_7b_attn", "llama2_7b_all", "llama3_8b_gqa_all", "llama2_13b_all"])
+def test_full_size_models_every_element(oracle, name):
+    """EVERY element of EVERY matrix of the full model after one token of the SWAP sequence
+    (token T/2, reached through the sequence's previous decision), streamed matrix by matrix."""
+    wl = wlmod.WORKLOADS[name]
+    m = DeviceModel(wl, gen_device="cuda", sentinel=True)
+    hidx, hg, idx, gates = oracle_decisions(oracle, m.hidden, m.router, wl.k)
+    t = wl.T // 2
+    m.ctx.fused_switch(None, None, idx[t - 1], gates[t - 1], wl.k, wl.scale, af.MERGE)
+    m.ctx.fused_switch(idx[t - 1], gates[t - 1], idx[t], gates[t], wl.k, wl.scale, af.SWAP)
+    _sync()
+    tally = Tally()
+    for mi, mat in enumerate(m.mats):
+        tally.add(check_full(oracle, mat, hidx[t], hg[t], wl.scale), ULP_TOL, (name, mi))
+        if mi % 8 == 7:
+            print(f"[{name}] matrix {mi + 1} of {len(m.mats)}: {tally.n} elements so far, differing {tally.diff}", flush=True)
+    tally.finish(MAX_DIFF_FRACTION)
+    assert tally.n == wl.elements
+    print(f"\n[{name}] ALL {tally.n} elements, differing {tally.diff}, cancellation cases {tally.cancel}")
     m.close()
 
 
