@@ -185,9 +185,9 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
         for (int s2 = 0; s2 < KCH; ++s2)
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                // rank index 16 (KCH kc + s2) + 8h + i; beyond a padded rank the read is outside the slice (zero) and cleared
-                const uint32_t v = ld_buffer_b32(rs, xoff, (uint32_t)(16 * (KCH * kc + s2) + i) * in_bytes);
-                x.d[s2][i] = (kPadded && 8 * h + i >= R) ? 0u : v;
+                // rank index 16 (KCH kc + s2) + 8h + i; beyond a padded rank the read is outside the
+                // expert's slice, for which the descriptor's range check returns zero
+                x.d[s2][i] = ld_buffer_b32(rs, xoff, (uint32_t)(16 * (KCH * kc + s2) + i) * in_bytes);
             }
     };
 
@@ -638,8 +638,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams 
         for (int s2 = 0; s2 < KCH; ++s2)
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const uint32_t v = ld_buffer_b32(rs, xoff, (uint32_t)(16 * (KCH * kc + s2) + i) * in_bytes);
-                x.d[s2][i] = (kPadded && 8 * h + i >= R) ? 0u : v;
+                x.d[s2][i] = ld_buffer_b32(rs, xoff, (uint32_t)(16 * (KCH * kc + s2) + i) * in_bytes);  // zero beyond a padded rank (range check)
             }
     };
     auto term_coeff = [&](int j) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(s_c[j]))); };
