@@ -66,6 +66,77 @@ __device__ __forceinline__ uint4_t *w_slot(uint16_t (*s_w)[TC], int row, int pie
     return reinterpret_cast<uint4_t *>(&s_w[row][8 * (piece ^ (row & 31))]);
 }
 
+// ---- the W tile's way in and out, shared by the three kernel forms ------------------
+// Request: row-contiguous non-temporal 128-bit loads, thread q takes the pieces
+// q, q + NTHR, ...; rows and columns beyond the matrix edge are clamped to valid
+// ones (unconditional loads schedule freely) and are never stored.
+template <int TC, int NTHR, int WQ>
+__device__ __forceinline__ void w_tile_request(uint4_t (&wreg)[WQ], const TileDev &tile, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < WQ; ++i) {
+        const int q = tid + NTHR * i;
+        const int row = q / (TC / 8), pc = q % (TC / 8);
+        const int cr = row < tile.rows_left ? row : tile.rows_left - 1;
+        const int cc = 8 * pc < tile.cols_left ? 8 * pc : tile.cols_left - 8;
+        wreg[i] = ld_global_nt(reinterpret_cast<const uint4_t *>(tile.w_src + (size_t)cr * tile.ldw + cc));
+    }
+}
+// Park: the same pieces into LDS as they land.
+template <int TC, int NTHR, int WQ>
+__device__ __forceinline__ void w_tile_park(uint16_t (*s_w)[TC], const uint4_t (&wreg)[WQ], int tid)
+{
+#pragma unroll
+    for (int i = 0; i < WQ; ++i) {
+        const int q = tid + NTHR * i;
+        *w_slot<TC>(s_w, q / (TC / 8), q % (TC / 8)) = wreg[i];
+    }
+}
+// Epilogue: each lane updates its pieces of the W tile in LDS, in the MFMA result
+// layout (row 32 rb + n of the wave's rows; column p of the 16-column group b is
+// accumulator cb = p & 1, v = 4 b + p / 2): W' = rn_bf16(W + c * acc), W added last.
+template <int TC>
+__device__ __forceinline__ void w_tile_update(uint16_t (*s_w)[TC], const float16_t (&acc)[2][2], float c, int lrow0, int lcol0, int n, int h)
+{
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            uint4_t *slot = w_slot<TC>(s_w, lrow0 + 32 * rb + n, lcol0 / 8 + 2 * b + h);
+            const uint4_t wv = *slot;
+            float o[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) o[q] = c * acc[rb][q & 1][4 * b + (q >> 1)];
+            uint4_t out;
+#pragma unroll
+            for (int hh = 0; hh < 4; ++hh)
+                out[hh] = pack_bf16_rne(o[2 * hh] + bf16_lo(wv[hh]), o[2 * hh + 1] + bf16_hi(wv[hh]));
+            *slot = out;
+        }
+}
+// The write-back addresses are the ones the tile was parked with.  The kernels derive
+// them again from an opaque copy of the thread index: kept alive across the
+// contraction they cost registers (a workgroup per CU where the budget is exact) or are
+// spilled, and every reload from scratch memory is a full memory round trip at the end
+// of the workgroup's life.
+__device__ __forceinline__ int opaque_copy(int v)
+{
+    asm volatile("" : "+v"(v));
+    return v;
+}
+// Write-back: the pieces go out the way they came in; nothing beyond the edge.
+template <int TC, int NTHR, int WQ>
+__device__ __forceinline__ void w_tile_store(uint16_t (*s_w)[TC], const TileDev &tile, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < WQ; ++i) {
+        const int q = tid + NTHR * i;
+        const int row = q / (TC / 8), pc = q % (TC / 8);
+        if (row < tile.rows_left && 8 * pc < tile.cols_left)
+            st_global_nt(*w_slot<TC>(s_w, row, pc), reinterpret_cast<uint4_t *>(tile.w_dst + (size_t)row * tile.ldw + 8 * pc));
+    }
+}
+
 template <int R, int NT>
 struct GemmPlan {
     static constexpr int KS = (R + 15) / 16;          // k-steps (16 rank indices) per expert
@@ -124,17 +195,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
     // operands go first and W last.
     constexpr bool kOperandsFirst = NT >= 4;
     uint4_t wreg[WQ];
-    auto request_w = [&]() {
-#pragma unroll
-        for (int i = 0; i < WQ; ++i) {
-            const int q = tid + NTHR * i;
-            const int row = q / (TC / 8), pc = q % (TC / 8);
-            const int cr = row < rows_left ? row : rows_left - 1;
-            const int cc = 8 * pc < cols_left ? 8 * pc : cols_left - 8;
-            wreg[i] = ld_global_nt(reinterpret_cast<const uint4_t *>(tile.w_src + (size_t)cr * ldw + cc));
-        }
-    };
-    if constexpr (!kOperandsFirst) request_w();
+    if constexpr (!kOperandsFirst) w_tile_request<TC, NTHR>(wreg, tile, tid);
 
     // Operand loads go through buffer descriptors: base and size of one expert's
     // slice in scalar registers, ONE 32-bit offset register per lane for all loads
@@ -200,18 +261,14 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
     for (int i = 0; i < QX; ++i)
         if (i / NCH < nt) fetch_x(xq[i], terms.e[i / NCH], i % NCH);
     if constexpr (kOperandsFirst) {
-        request_w();
+        w_tile_request<TC, NTHR>(wreg, tile, tid);
 #pragma unroll
         for (int j = 0; j < NB; ++j)
             if (j < nt) stash_b(vb[j], j);
     }
 
     // W tile and row operands into LDS as they land: the registers are free for the contraction
-#pragma unroll
-    for (int i = 0; i < WQ; ++i) {
-        const int q = tid + NTHR * i;
-        *w_slot<TC>(s_w, q / (TC / 8), q % (TC / 8)) = wreg[i];
-    }
+    w_tile_park<TC, NTHR>(s_w, wreg, tid);
     if constexpr (!kOperandsFirst) {
 #pragma unroll
         for (int j = 0; j < NB; ++j)
@@ -291,32 +348,10 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
 
     // ---- epilogue: each lane updates its pieces of the W tile in LDS, in the result
     // layout (column p of a group is accumulator cb = p&1, v = 4b + p/2); tile back out.
-    if (c_last != 0.0f) {  // no term, or only zero coefficients: the bits pass through untouched (-0.0 stays -0.0)
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                uint4_t *slot = w_slot<TC>(s_w, 32 * rb + n, lcol0 / 8 + 2 * b + h);
-                const uint4_t wv = *slot;
-                float o[8];
-#pragma unroll
-                for (int q = 0; q < 8; ++q) o[q] = c_last * acc[rb][q & 1][4 * b + (q >> 1)];
-                uint4_t out;
-#pragma unroll
-                for (int hh = 0; hh < 4; ++hh)
-                    out[hh] = pack_bf16_rne(o[2 * hh] + bf16_lo(wv[hh]), o[2 * hh + 1] + bf16_hi(wv[hh]));
-                *slot = out;
-            }
-    }
+    // no term, or only zero coefficients: the bits pass through untouched (-0.0 stays -0.0)
+    if (c_last != 0.0f) w_tile_update<TC>(s_w, acc, c_last, 0, lcol0, n, h);
     __syncthreads();
-#pragma unroll
-    for (int i = 0; i < WQ; ++i) {
-        const int q = tid + NTHR * i;
-        const int row = q / (TC / 8), pc = q % (TC / 8);
-        if (row < rows_left && 8 * pc < cols_left)
-            st_global_nt(*w_slot<TC>(s_w, row, pc),
-                         reinterpret_cast<uint4_t *>(tile.w_dst + (size_t)row * ldw + 8 * pc));
-    }
+    w_tile_store<TC, NTHR, WQ>(s_w, tile, opaque_copy(tid));
 }
 
 // The same contraction for long inner dimensions at ranks of 32 and more, where a
@@ -410,21 +445,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(4, 4)))
         if (NS + s < STEPS) fetch_b(vbq[s], NS + s);
 #pragma unroll
     for (int s = 0; s < XD; ++s) fetch_x(xq[s], s);
-#pragma unroll
-    for (int i = 0; i < WQ; ++i) {
-        const int q = tid + NTHR * i;
-        const int row = q / (TC / 8), pc = q % (TC / 8);
-        const int cr = row < rows_left ? row : rows_left - 1;
-        const int cc = 8 * pc < cols_left ? 8 * pc : cols_left - 8;
-        wreg[i] = ld_global_nt(reinterpret_cast<const uint4_t *>(tile.w_src + (size_t)cr * ldw + cc));
-    }
+    w_tile_request<TC, NTHR>(wreg, tile, tid);
 #pragma unroll
     for (int s = 0; s < NS; ++s) stash_b(vbu[s], s);
-#pragma unroll
-    for (int i = 0; i < WQ; ++i) {
-        const int q = tid + NTHR * i;
-        *w_slot<TC>(s_w, q / (TC / 8), q % (TC / 8)) = wreg[i];
-    }
+    w_tile_park<TC, NTHR>(s_w, wreg, tid);
     __syncthreads();
 
     float16_t acc[2][2];
@@ -475,38 +499,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(4, 4)))
         }
     }
 
-    // ---- epilogue and write-back (as in switch_gemm_kernel)
-    if (c_last != 0.0f) {
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                uint4_t *slot = w_slot<TC>(s_w, 32 * rb + n, lcol0 / 8 + 2 * b + h);
-                const uint4_t wv = *slot;
-                float o[8];
-#pragma unroll
-                for (int q = 0; q < 8; ++q) o[q] = c_last * acc[rb][q & 1][4 * b + (q >> 1)];
-                uint4_t out;
-#pragma unroll
-                for (int hh = 0; hh < 4; ++hh)
-                    out[hh] = pack_bf16_rne(o[2 * hh] + bf16_lo(wv[hh]), o[2 * hh + 1] + bf16_hi(wv[hh]));
-                *slot = out;
-            }
-    }
+    // ---- epilogue and write-back
+    if (c_last != 0.0f) w_tile_update<TC>(s_w, acc, c_last, 0, lcol0, n, h);
     __syncthreads();
-    // The write-back addresses are the ones the tile was parked with.  Derive them
-    // again from an opaque copy of the thread index: kept alive across the
-    // contraction they would be spilled, and every reload from scratch memory is
-    // a full memory round trip at the end of the workgroup's life.
-    int tid_out = tid;
-    asm volatile("" : "+v"(tid_out));
-#pragma unroll
-    for (int i = 0; i < WQ; ++i) {
-        const int q = tid_out + NTHR * i;
-        const int row = q / (TC / 8), pc = q % (TC / 8);
-        if (row < rows_left && 8 * pc < cols_left)
-            st_global_nt(*w_slot<TC>(s_w, row, pc), reinterpret_cast<uint4_t *>(tile.w_dst + (size_t)row * ldw + 8 * pc));
-    }
+    w_tile_store<TC, NTHR, WQ>(s_w, tile, opaque_copy(tid));
 }
 
 // The same kernel for many experts (4 or more terms): a run-time loop over the
@@ -567,14 +563,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams 
     // read a clamped (valid) address -- unconditional loads schedule freely -- and
     // are never stored.
     uint4_t wreg[WQ];
-#pragma unroll
-    for (int i = 0; i < WQ; ++i) {
-        const int q = tid + NTHR * i;
-        const int row = q / (TC / 8), pc = q % (TC / 8);
-        const int cr = row < rows_left ? row : rows_left - 1;
-        const int cc = 8 * pc < cols_left ? 8 * pc : cols_left - 8;
-        wreg[i] = ld_global_nt(reinterpret_cast<const uint4_t *>(tile.w_src + (size_t)cr * ldw + cc));
-    }
+    w_tile_request<TC, NTHR>(wreg, tile, tid);
     __syncthreads();  // term list visible
 
     float16_t acc[2][2];
@@ -661,11 +650,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams 
     }
     // W tile into LDS now (its loads were issued first, so they are the first to land):
     // the registers are free for the contraction
-#pragma unroll
-    for (int i = 0; i < WQ; ++i) {
-        const int q = tid + NTHR * i;
-        *w_slot<TC>(s_w, q / (TC / 8), q % (TC / 8)) = wreg[i];
-    }
+    w_tile_park<TC, NTHR>(s_w, wreg, tid);
     if (j < nt) stash_b(vb, 0);
     __syncthreads();
     while (j < nt) {
@@ -719,32 +704,10 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams 
 
     // ---- epilogue: each lane updates its pieces of the W tile in LDS, in the result
     // layout (column p of a group is accumulator cb = p&1, v = 4b + p/2); tile back out.
-    if (c_last != 0.0f) {  // no term, or only zero coefficients: the bits pass through untouched (-0.0 stays -0.0)
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                uint4_t *slot = w_slot<TC>(s_w, lrow0 + 32 * rb + n, lcol0 / 8 + 2 * b + h);
-                const uint4_t wv = *slot;
-                float o[8];
-#pragma unroll
-                for (int q = 0; q < 8; ++q) o[q] = c_last * acc[rb][q & 1][4 * b + (q >> 1)];
-                uint4_t out;
-#pragma unroll
-                for (int hh = 0; hh < 4; ++hh)
-                    out[hh] = pack_bf16_rne(o[2 * hh] + bf16_lo(wv[hh]), o[2 * hh + 1] + bf16_hi(wv[hh]));
-                *slot = out;
-            }
-    }
+    // no term, or only zero coefficients: the bits pass through untouched (-0.0 stays -0.0)
+    if (c_last != 0.0f) w_tile_update<TC>(s_w, acc, c_last, lrow0, lcol0, n, h);
     __syncthreads();
-#pragma unroll
-    for (int i = 0; i < WQ; ++i) {
-        const int q = tid + NTHR * i;
-        const int row = q / (TC / 8), pc = q % (TC / 8);
-        if (row < rows_left && 8 * pc < cols_left)
-            st_global_nt(*w_slot<TC>(s_w, row, pc),
-                         reinterpret_cast<uint4_t *>(tile.w_dst + (size_t)row * ldw + 8 * pc));
-    }
+    w_tile_store<TC, NTHR, WQ>(s_w, tile, opaque_copy(tid));
 }
 
 }  // namespace adafuse
