@@ -79,7 +79,10 @@ WORKLOADS = {
     "llama2_13b_all": Workload("llama2_13b_all", 40, 5120, _attn(5120) + _mlp(5120, 13824),
                                E=8, r=16, k=2, T=512, seed=5, repeat_prob=0.3),
 }
-# beyond the five graded configurations: the ranks the paper calls typical (64 or 128, top-2)
+# beyond the five graded configurations: the ranks the paper calls typical (64 or 128, top-2),
+# and rank 32 between them and the graded ones
+WORKLOADS["llama2_7b_all_r32"] = Workload("llama2_7b_all_r32", 32, 4096, _attn(4096) + _mlp(4096, 11008),
+                                          E=8, r=32, k=2, T=64, seed=8)
 WORKLOADS["llama2_7b_all_r64"] = Workload("llama2_7b_all_r64", 32, 4096, _attn(4096) + _mlp(4096, 11008),
                                           E=8, r=64, k=2, T=64, seed=6)
 WORKLOADS["llama2_7b_all_r128"] = Workload("llama2_7b_all_r128", 32, 4096, _attn(4096) + _mlp(4096, 11008),

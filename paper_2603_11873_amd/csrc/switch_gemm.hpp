@@ -144,17 +144,35 @@ struct GemmPlan {
     static constexpr int KCH = KS >= 2 ? 2 : 1;       // k-steps per column-operand chunk
     static constexpr int NCH = KS / KCH;              // chunks per expert
     static constexpr int TOT = NT * NCH;              // chunks per tile
-    static constexpr int QMAX = KCH == 1 ? 8 : 4;     // chunks in flight: at most 64 VGPRs
+    // Chunks in flight: at most 64 VGPRs.  Rank 128 takes half of that and one resident B
+    // slice (BMAX) to stay under 168 VGPRs and 53 KB of LDS: three workgroups per CU
+    // instead of two outweigh the shorter queue there (not so at rank 64).
+    static constexpr int QMAX = KCH == 1 ? 8 : (R >= 128 ? 2 : 4);
     static constexpr int QX = TOT < QMAX ? TOT : QMAX;
     static constexpr int RP = R < 8 ? 8 : R;          // rank padded to one 16-byte piece
     // LDS row pitch of a staged B slice (bf16).  One k-step per row (32 bytes) needs no
-    // pad: a wave's 64 reads of 16 bytes cover 1 KB contiguously.  Longer rows get 16 bytes.
-    static constexpr int BP = R <= 16 ? 16 : R + 8;
-    static constexpr int BMAX = R <= 16 ? 4 : 2;      // B slices resident in LDS (more cost a workgroup per CU)
+    // padding: a wave's 64 reads of 16 bytes cover 1 KB contiguously.  Rows of 2 or 4
+    // k-steps are not padded either: their 16-byte pieces are permuted by the row number
+    // (b_piece), so that the 16 rows a quarter-wave reads at one piece index fall on 16
+    // different bank groups.  Rank 128 keeps a 16-byte pad (the permuted addresses cost
+    // it the registers that decide its occupancy).
+    static constexpr int BP = R <= 16 ? 16 : (R >= 128 ? R + 8 : R);
+    static constexpr int PPRB = BP / 8;  // 16-byte pieces per row
+    __device__ static __forceinline__ int b_piece(int row, int piece)
+    {
+        if constexpr (R <= 16 || BP != R)
+            return piece;
+        else
+            return piece ^ ((row * PPRB / 16) & (PPRB - 1));
+    }
+    // B slices resident in LDS (more cost a workgroup per CU).  A further expert's slice is
+    // requested when the contraction of the expert whose slot it takes begins, and stored
+    // behind a barrier once that contraction is done.
+    static constexpr int BMAX = R <= 16 ? 4 : (R >= 128 ? 1 : 2);
     static constexpr int NB = NT < BMAX ? NT : BMAX;  // B slices resident
     static constexpr int BV = kGemmTileRows * RP / 8;  // 16-byte pieces of one expert's B slice
     static constexpr int BQ(int nthr) { return (BV + nthr - 1) / nthr; }  // ... per thread
-    static_assert(NB >= 2 || NT == 1, "rolling needs two resident slices");
+    static_assert(NB >= 2 || NT <= 2, "rolling more than one refill needs two resident slices");
 };
 
 template <int R, int NT, int NW>
@@ -225,7 +243,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
             const int q = tid + NTHR * i;
             const int row = q / (RP / 8), piece = q % (RP / 8);
             if (q < BV) {
-                *reinterpret_cast<uint4_t *>(&s_b[slot][row][8 * piece]) = v[i];
+                *reinterpret_cast<uint4_t *>(&s_b[slot][row][8 * P::b_piece(row, piece)]) = v[i];
                 if constexpr (kPadded)  // second half of the single k-step: zeros
                     *reinterpret_cast<uint4_t *>(&s_b[slot][row][8]) = uint4_t{0u, 0u, 0u, 0u};
             }
@@ -327,7 +345,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
                     const int ks = kc * KCH + s2;
 #pragma unroll
                     for (int rb = 0; rb < 2; ++rb) {
-                        const uint4_t y = *reinterpret_cast<const uint4_t *>(&s_b[j % NB][32 * rb + n][16 * ks + 8 * h]);
+                        const uint4_t y = *reinterpret_cast<const uint4_t *>(&s_b[j % NB][32 * rb + n][8 * P::b_piece(32 * rb + n, 2 * ks + h)]);
                         const bf16x8_t yy = __builtin_bit_cast(bf16x8_t, y);
                         acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0[s2], yy, acc[rb][0], 0, 0, 0);
                         acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1[s2], yy, acc[rb][1], 0, 0, 0);
