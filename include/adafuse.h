@@ -43,7 +43,7 @@ typedef enum {
     ADAFUSE_ERR_ARG = 2,   /* a scalar argument is out of range */
     ADAFUSE_ERR_SHAPE = 3, /* a matrix shape is unsupported */
     ADAFUSE_ERR_ALIGN = 4, /* a pointer or leading dimension is misaligned */
-    ADAFUSE_ERR_HIP = 5    /* a HIP runtime call failed */
+    ADAFUSE_ERR_HIP = 5    /* a HIP runtime call or a host allocation failed */
 } adafuse_status;
 
 typedef enum {
@@ -120,7 +120,9 @@ adafuse_status adafuse_create(const adafuse_matrix_desc *mats, int32_t n_mats,
 adafuse_status adafuse_destroy(adafuse_ctx *ctx);
 
 /* Choose the switch kernel (adafuse_kernel).  Rebuilds the tile table if the
- * tile shape changes (allocates and synchronises like adafuse_create). */
+ * tile shape changes (allocates and synchronises like adafuse_create; the
+ * context's device must be current, else ERR_ARG).  On any error the context
+ * keeps the kernel and tables it had. */
 adafuse_status adafuse_set_kernel(adafuse_ctx *ctx, int32_t kernel);
 
 /* Fill *info (HOST) with the context's geometry. */

@@ -271,18 +271,20 @@ void deal_to_xcds(std::vector<TileDev> &v, size_t begin, size_t end, size_t G)
 // while that matrix streams through.
 adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
 {
+    // everything is built aside and handed to the context at the end: a failure leaves it as it was
     int tr = kValuTileRows, tc = kValuTileCols;
+    int mfma_shape = c->mfma_shape, gemm_waves = c->gemm_waves, order = c->order;
     if (kernel == ADAFUSE_KERNEL_MFMA) {
-        c->mfma_shape = pick_shape(c->r, max_terms(c));
-        with_shape(c->mfma_shape, [&](auto sh) {
+        mfma_shape = pick_shape(c->r, max_terms(c));
+        with_shape(mfma_shape, [&](auto sh) {
             tr = decltype(sh)::TR;
             tc = decltype(sh)::TC;
             return true;
         });
     } else if (kernel == ADAFUSE_KERNEL_GEMM) {
-        if (const char *e = std::getenv("ADAFUSE_GEMM_WAVES")) c->gemm_waves = std::atoi(e) == 8 ? 8 : 4;
+        if (const char *e = std::getenv("ADAFUSE_GEMM_WAVES")) gemm_waves = std::atoi(e) == 8 ? 8 : 4;
         tr = kGemmTileRows;
-        tc = kGemmWaveCols * c->gemm_waves;
+        tc = kGemmWaveCols * gemm_waves;
     }
     std::vector<MatDev> hm(c->mats.size());
     std::vector<TileDev> ht;
@@ -305,18 +307,19 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
         mat_off.push_back((int64_t)ht.size());
     }
     if (ht.size() > 0x3fffffffu) return ADAFUSE_ERR_SHAPE;
-    if (const char *e = std::getenv("ADAFUSE_ORDER")) c->order = std::atoi(e);
+    if (const char *e = std::getenv("ADAFUSE_ORDER")) order = std::atoi(e);
     // second section: the same tiles grouped per matrix, for the one-launch-per-matrix form
     const size_t n = ht.size();
     ht.insert(ht.end(), ht.begin(), ht.begin() + n);
-    if (c->order >= 1) {
-        auto run = [&](size_t count) { return c->order == 1 ? (count + 7) / 8 : (size_t)c->order; };
+    if (order >= 1) {
+        auto run = [&](size_t count) { return order == 1 ? (count + 7) / 8 : (size_t)order; };
         deal_to_xcds(ht, 0, n, run(n));
         for (size_t i = 0; i + 1 < mat_off.size(); ++i)
             deal_to_xcds(ht, n + mat_off[i], n + mat_off[i + 1], run((size_t)(mat_off[i + 1] - mat_off[i])));
     }
 
-    if (hipGetDevice(&c->device) != hipSuccess) return ADAFUSE_ERR_HIP;
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) return ADAFUSE_ERR_HIP;
     MatDev *dm = nullptr;
     TileDev *dt = nullptr;
     if (hipMalloc(&dm, hm.size() * sizeof(MatDev)) != hipSuccess) return ADAFUSE_ERR_HIP;
@@ -333,7 +336,11 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
     free_tables(c);
     c->d_mats = dm;
     c->d_tiles = dt;
+    c->device = device;
     c->kernel = kernel;
+    c->mfma_shape = mfma_shape;
+    c->gemm_waves = gemm_waves;
+    c->order = order;
     c->tile_rows = tr;
     c->tile_cols = tc;
     c->n_tiles = (int64_t)n;
@@ -353,19 +360,21 @@ adafuse_status adafuse_create(const adafuse_matrix_desc *mats, int32_t n_mats, i
     *ctx = nullptr;
     adafuse_status st = validate_mats(mats, n_mats, E, r, k_max);
     if (st != ADAFUSE_OK) return st;
+    if (mats[0].w_base == mats[0].w_work && 2 * k_max > kMaxTerms) return ADAFUSE_ERR_ARG;  // an in-place SWAP carries 2k terms
     adafuse_ctx *c = new (std::nothrow) adafuse_ctx();
     if (!c) return ADAFUSE_ERR_HIP;
-    c->mats.assign(mats, mats + n_mats);
-    c->E = E;
-    c->r = r;
-    c->k_max = k_max;
-    c->inplace = mats[0].w_base == mats[0].w_work;
-    if (c->inplace && 2 * k_max > kMaxTerms) {  // an in-place SWAP carries 2k terms
-        delete c;
-        return ADAFUSE_ERR_ARG;
+    try {  // the host tables are std::vectors: no exception may cross the C boundary
+        c->mats.assign(mats, mats + n_mats);
+        c->E = E;
+        c->r = r;
+        c->k_max = k_max;
+        c->inplace = mats[0].w_base == mats[0].w_work;
+        st = build_tables(c, auto_kernel(r, max_terms(c)));
+    } catch (...) {
+        st = ADAFUSE_ERR_HIP;
     }
-    st = build_tables(c, auto_kernel(r, max_terms(c)));
     if (st != ADAFUSE_OK) {
+        free_tables(c);
         delete c;
         return st;
     }
@@ -390,8 +399,13 @@ adafuse_status adafuse_set_kernel(adafuse_ctx *ctx, int32_t kernel)
     if (kernel == ADAFUSE_KERNEL_MFMA && !mfma_supported(ctx->r, max_terms(ctx))) return ADAFUSE_ERR_ARG;
     if (kernel == ADAFUSE_KERNEL_GEMM && !gemm_supported(ctx->r)) return ADAFUSE_ERR_ARG;
     if (kernel == ctx->kernel) return ADAFUSE_OK;
+    if (!on_ctx_device(ctx)) return ADAFUSE_ERR_ARG;
     if (hipDeviceSynchronize() != hipSuccess) return ADAFUSE_ERR_HIP;  // no launch may still read the old table
-    return build_tables(ctx, kernel);
+    try {
+        return build_tables(ctx, kernel);  // on failure the context keeps its old tables and kernel
+    } catch (...) {
+        return ADAFUSE_ERR_HIP;
+    }
 }
 
 adafuse_status adafuse_get_info(const adafuse_ctx *ctx, adafuse_info *info)
