@@ -13,6 +13,7 @@
 #include "forward.hpp"
 #include "pregate.hpp"
 #include "switch_gemm.hpp"
+#include "switch_gemm_overlap.hpp"
 #include "switch_mfma.hpp"
 #include "switch_valu.hpp"
 
@@ -128,38 +129,44 @@ bool launch_mfma_any(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t
     }
 }
 
+// Which form runs (R, terms): the unrolled kernel up to 7 k-steps of 16 rank indices per
+// tile, the overlapped one (W straight into LDS, contraction meanwhile) for 8 to 16, the
+// run-time expert loop beyond.  Measurement knob ADAFUSE_GEMM_FORM: 1 = never the
+// overlapped form, 2 = the expert loop for every launch with 4 or more terms.
+template <int R, int NT, int NW>
+bool launch_gemm_form(const SwitchParams &p, int64_t n_tiles, hipStream_t s)
+{
+    const dim3 grid((unsigned)n_tiles), block(64 * NW);
+    static const int form = [] { const char *e = std::getenv("ADAFUSE_GEMM_FORM"); return e ? std::atoi(e) : 0; }();
+    constexpr int steps = NT * ((R + 15) / 16);
+    constexpr bool can_unroll = NT <= 2 || (NT == 4 && R <= 16);  // every row operand fits beside the W tile
+    if constexpr (R % 16 == 0 && steps <= 16) {
+        if ((steps >= 8 || form == 3) && form != 1 && !(form == 2 && NT >= 4)) {
+            hipLaunchKernelGGL((switch_gemm_overlap_kernel<R, NT, NW>), grid, block, 0, s, p);
+            return true;
+        }
+    }
+    if constexpr (can_unroll) {
+        if (!(form == 2 && NT >= 4)) {
+            hipLaunchKernelGGL((switch_gemm_kernel<R, NT, NW>), grid, block, 0, s, p);
+            return true;
+        }
+    }
+    if constexpr (NT >= 4) {
+        hipLaunchKernelGGL((switch_gemm_loop_kernel<R, NW>), grid, block, 0, s, p);
+        return true;
+    }
+    return false;
+}
+
 template <int R, int NW>
 bool launch_gemm_rw(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t s)
 {
-    const dim3 grid((unsigned)n_tiles), block(64 * NW);
-    // ADAFUSE_GEMM_FORM=2 keeps the run-time expert loop for every launch with 4 terms (a measurement knob)
-    static const bool looped = [] { const char *e = std::getenv("ADAFUSE_GEMM_FORM"); return e && std::atoi(e) == 2; }();
     switch (nt) {
-    case 1: hipLaunchKernelGGL((switch_gemm_kernel<R, 1, NW>), grid, block, 0, s, p); return true;
-    case 2: hipLaunchKernelGGL((switch_gemm_kernel<R, 2, NW>), grid, block, 0, s, p); return true;
-    case 4:
-        if constexpr (R <= 16) {  // all four row operands fit beside the W tile: unrolled, no barrier in the contraction
-            if (!looped) {
-                hipLaunchKernelGGL((switch_gemm_kernel<R, 4, NW>), grid, block, 0, s, p);
-                return true;
-            }
-        } else if constexpr (R <= 64) {  // 8 or 16 k-steps through the ring of row-operand pieces
-            if (!looped) {
-                hipLaunchKernelGGL((switch_gemm_ring_kernel<R, 4, NW>), grid, block, 0, s, p);
-                return true;
-            }
-        }
-        hipLaunchKernelGGL((switch_gemm_loop_kernel<R, NW>), grid, block, 0, s, p);
-        return true;
-    case 8:
-        if constexpr (R == 16) {  // 8 k-steps through the ring
-            if (!looped) {
-                hipLaunchKernelGGL((switch_gemm_ring_kernel<R, 8, NW>), grid, block, 0, s, p);
-                return true;
-            }
-        }
-        hipLaunchKernelGGL((switch_gemm_loop_kernel<R, NW>), grid, block, 0, s, p);
-        return true;
+    case 1: return launch_gemm_form<R, 1, NW>(p, n_tiles, s);
+    case 2: return launch_gemm_form<R, 2, NW>(p, n_tiles, s);
+    case 4: return launch_gemm_form<R, 4, NW>(p, n_tiles, s);
+    case 8: return launch_gemm_form<R, 8, NW>(p, n_tiles, s);
     default: return false;
     }
 }

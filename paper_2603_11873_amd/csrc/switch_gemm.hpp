@@ -35,11 +35,12 @@
 // The W tile sits in LDS unpadded (32 KB), its 16-byte pieces permuted by the
 // row number (w_slot), which leaves 8 KB of a four-workgroups-per-CU share of
 // LDS for the row operands.
-// Three forms: switch_gemm_kernel<R, NT> for 1 or 2 terms at any rank and 4
-// terms up to rank 16, fully unrolled with every row operand resident;
-// switch_gemm_ring_kernel<R, NT> for 4 terms at ranks 32 and 64 and 8 terms at
-// rank 16 (8 or 16 k-steps through a ring of 2 KB row-operand pieces);
-// switch_gemm_loop_kernel<R> for the rest: a run-time loop over the experts.
+// Three forms, by the number of k-steps (16 rank indices of one expert) a tile
+// takes: switch_gemm_kernel<R, NT> below, fully unrolled with every row operand
+// resident, up to 7; switch_gemm_overlap_kernel<R, NT> (its own header) for 8 to
+// 16, where the contraction is long enough to be worth running while the W tile
+// is still on its way; switch_gemm_loop_kernel<R> for the rest: a run-time loop
+// over the experts.
 // Gates stay out of the bf16 operands.  Experts are chained in ONE accumulator:
 //   acc = P_0;  acc = acc * (c_0/c_1) + P_1;  ...;  W' = rn_bf16(W + c_last * acc)
 // which equals W + sum_j c_j P_j up to fp32 rounding of the ratios (terms with a
@@ -367,157 +368,6 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
     // ---- epilogue: each lane updates its pieces of the W tile in LDS, in the result
     // layout (column p of a group is accumulator cb = p&1, v = 4b + p/2); tile back out.
     // no term, or only zero coefficients: the bits pass through untouched (-0.0 stays -0.0)
-    if (c_last != 0.0f) w_tile_update<TC>(s_w, acc, c_last, 0, lcol0, n, h);
-    __syncthreads();
-    w_tile_store<TC, NTHR, WQ>(s_w, tile, opaque_copy(tid));
-}
-
-// The same contraction for long inner dimensions at ranks of 32 and more, where a
-// whole B slice per expert would cost workgroups per CU: the unit is ONE k-step
-// (16 rank indices of one expert), fully unrolled over all NT * R/16 of them.  The
-// row operand of a k-step is a 64 x 16 piece of 2 KB; four of them sit in a ring
-// in LDS, the next BD are in registers on their way, and a piece moves into the
-// ring slot of the k-step that has just been consumed (one barrier per k-step
-// once the ring turns).  With the unpadded W tile that is exactly 40 KB: four
-// workgroups per CU at every rank.  Used for 4 terms (in place with top-2, or
-// top-4), where it beats the run-time expert loop by 8 % (rank 32) to 27 % (rank
-// 64); with 1 or 2 terms the unrolled kernel above is faster (its contraction
-// has no barrier) and is used instead.
-template <int R, int NT, int NW>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(4, 4))) void switch_gemm_ring_kernel(SwitchParams p)
-{
-    static_assert(R % 16 == 0, "whole k-steps");
-    constexpr int KS = R / 16;          // k-steps per expert
-    constexpr int STEPS = NT * KS;      // k-steps per tile
-    constexpr int NS = 4;               // ring slots
-    constexpr int XD = STEPS > 4 ? 3 : 4;  // column-operand k-steps in flight (8 registers each); the budget is 128 in all
-    constexpr int BD = 2;               // row-operand pieces in flight beyond the ring (8 or 4 bytes per thread each)
-    constexpr int NTHR = 64 * NW;
-    constexpr int TR = kGemmTileRows, TC = kGemmWaveCols * NW;
-    constexpr int WQ = TR * TC / 8 / NTHR;
-    constexpr int BB = TR * 32 / NTHR;  // bytes of one k-step of the row operand (64 rows x 32 B) per thread: every thread takes part
-    static_assert(STEPS >= NS && STEPS <= 16, "4 to 16 k-steps");
-    static_assert(BB == 8 || BB == 4, "4 or 8 waves");
-    using BPiece = typename std::conditional<BB == 8, uint2_t, uint32_t>::type;
-
-    __shared__ __align__(16) uint16_t s_b[NS][TR][16];
-    __shared__ __align__(16) uint16_t s_w[TR][TC];  // pieces permuted: w_slot
-
-    Terms terms;
-    if (!load_terms<NT>(p, terms)) return;
-    const int nt = p.inplace ? (p.mode == 2 ? 2 * p.k : p.k) : p.k;
-
-    const TileDev tile = p.tiles[blockIdx.x];
-    const MatDev m = p.mats[tile.mat];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wc = tid >> 6;
-    const int n = lane & 31;
-    const int h = lane >> 5;
-    const int lcol0 = 64 * wc;
-    const int rows_left = tile.rows_left, cols_left = tile.cols_left;
-    const int ldw = tile.ldw;
-
-    // operand addressing: one descriptor per expert, one offset register per lane
-    int acol = lcol0 + 2 * n;
-    acol = tile.col0 + (acol < cols_left ? acol : cols_left - 2);
-    const uint32_t in_bytes = 2u * (uint32_t)m.in;
-    const uint32_t xoff = 8u * h * in_bytes + 2u * (uint32_t)acol;
-    constexpr int BPR = 32 / BB;  // threads per row of the piece
-    const int brow = tid / BPR < rows_left ? tid / BPR : rows_left - 1;
-    const uint32_t boff = 2u * (uint32_t)brow * R + (uint32_t)BB * (tid % BPR);
-    const uint32_t b_bytes = (uint32_t)(m.out - tile.row0) * R * 2u;
-    // A k-step of an expert that is not in use (beyond the token's k, or with a zero
-    // coefficient) gets an empty descriptor: its loads return zeros without touching
-    // memory and its MFMAs add nothing, so the whole contraction is straight-line
-    // code with exact wait counts -- no branch depends on the term list.
-    auto in_use = [&](int step) { return step / KS < nt && terms.c[step / KS] != 0.0f; };  // step: a constant after unrolling
-    auto fetch_b = [&](BPiece &v, int step) {
-        const __amdgpu_buffer_rsrc_t rs =
-            make_buffer(m.b_bank + ((size_t)terms.e[step / KS] * m.out + tile.row0) * R, in_use(step) ? b_bytes : 0u);
-        if constexpr (BB == 8)
-            v = ld_buffer_b64(rs, boff, 32u * (step % KS));
-        else
-            v = ld_buffer_b32(rs, boff, 32u * (step % KS));
-    };
-    auto stash_b = [&](const BPiece &v, int slot) {
-        *reinterpret_cast<BPiece *>(&s_b[slot][tid / BPR][(BB / 2) * (tid % BPR)]) = v;
-    };
-    auto fetch_x = [&](uint32_t (&d)[8], int step) {
-        // the k-step goes into the descriptor's base, so the uniform offsets (i rows of the bank) are the same 8 for every k-step
-        const __amdgpu_buffer_rsrc_t rs = make_buffer(m.a_bank + ((size_t)terms.e[step / KS] * R + 16 * (step % KS)) * m.in,
-                                                      in_use(step) ? 16u * in_bytes : 0u);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) d[i] = ld_buffer_b32(rs, xoff, (uint32_t)i * in_bytes);
-    };
-
-    // ---- requests: the operands of the first k-steps, then W (loads return in issue
-    // order; see the note on that order in switch_gemm_kernel)
-    BPiece vbu[NS], vbq[BD];
-    uint32_t xq[XD][8];
-    uint4_t wreg[WQ];
-#pragma unroll
-    for (int s = 0; s < NS; ++s) fetch_b(vbu[s], s);
-#pragma unroll
-    for (int s = 0; s < BD; ++s)
-        if (NS + s < STEPS) fetch_b(vbq[s], NS + s);
-#pragma unroll
-    for (int s = 0; s < XD; ++s) fetch_x(xq[s], s);
-    w_tile_request<TC, NTHR>(wreg, tile, tid);
-#pragma unroll
-    for (int s = 0; s < NS; ++s) stash_b(vbu[s], s);
-    w_tile_park<TC, NTHR>(s_w, wreg, tid);
-    __syncthreads();
-
-    float16_t acc[2][2];
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.0f;
-
-    float c_last = 0.0f;
-#pragma unroll
-    for (int s = 0; s < STEPS; ++s) {
-        if (s % KS == 0 && in_use(s)) {  // a new expert: rescale what is accumulated so far (uniform branch, no loads inside)
-            const float c = terms.c[s / KS];
-            if (c_last != 0.0f) {
-                const float ratio = c_last / c;
-#pragma unroll
-                for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                    for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) acc[rb][cb][v] *= ratio;
-            }
-            c_last = c;
-        }
-        const uint32_t *d = xq[s % XD];
-        const uint4_t xe = {__builtin_amdgcn_perm(d[1], d[0], 0x05040100u), __builtin_amdgcn_perm(d[3], d[2], 0x05040100u),
-                            __builtin_amdgcn_perm(d[5], d[4], 0x05040100u), __builtin_amdgcn_perm(d[7], d[6], 0x05040100u)};
-        const uint4_t xo = {__builtin_amdgcn_perm(d[1], d[0], 0x07060302u), __builtin_amdgcn_perm(d[3], d[2], 0x07060302u),
-                            __builtin_amdgcn_perm(d[5], d[4], 0x07060302u), __builtin_amdgcn_perm(d[7], d[6], 0x07060302u)};
-        const bf16x8_t x0 = __builtin_bit_cast(bf16x8_t, xe), x1 = __builtin_bit_cast(bf16x8_t, xo);
-        if (s + XD < STEPS) fetch_x(xq[s % XD], s + XD);  // the slot is consumed: refill it
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            const uint4_t y = *reinterpret_cast<const uint4_t *>(&s_b[s % NS][32 * rb + n][8 * h]);
-            const bf16x8_t yy = __builtin_bit_cast(bf16x8_t, y);
-            acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0, yy, acc[rb][0], 0, 0, 0);
-            acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1, yy, acc[rb][1], 0, 0, 0);
-        }
-        if (s + NS < STEPS) {  // the ring turns: k-step s + NS takes this slot
-            __syncthreads();   // every wave is done reading it
-            stash_b(vbq[s % BD], s % NS);
-            if (s + NS + BD < STEPS) fetch_b(vbq[s % BD], s + NS + BD);
-            // the refill is visible to its readers through the barrier of the next
-            // k-step, or, when no further slot turns, through this one
-            if (s + 1 + NS >= STEPS) __syncthreads();
-        }
-    }
-
-    // ---- epilogue and write-back
     if (c_last != 0.0f) w_tile_update<TC>(s_w, acc, c_last, 0, lcol0, n, h);
     __syncthreads();
     w_tile_store<TC, NTHR, WQ>(s_w, tile, opaque_copy(tid));

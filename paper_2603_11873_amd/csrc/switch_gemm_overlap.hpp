@@ -1,0 +1,249 @@
+// Fused switch, rank-looped form for long contractions (8 to 16 k-steps of 16 rank
+// indices per tile: top-2 at ranks 64 and 128, four terms at ranks 32 and 64, ...).
+// Same tile, same MFMA arrangement, same arithmetic and same write-back as
+// switch_gemm_kernel.  Two things differ.
+//
+// 1. The W tile goes straight into LDS (buffer_load ... lds: no registers, no park
+//    step), requested AFTER the operands, and is first looked at by the epilogue:
+//      request row operands, column operands, then W (loads return in issue order,
+//      so the cache-resident operands are not queued behind the W tile);
+//      row operands into LDS; contraction while W lands; wait for W; epilogue.
+//    The transfer has to be the buffer form: for it the compiler keeps exact wait
+//    counts and knows that accesses to the row-operand array cannot touch the W
+//    tile's landing zone, whereas after a global_load_lds it waits for everything
+//    before any LDS access.  The barrier that publishes the row operands must not
+//    wait for the transfer either, so it is the bare instruction behind a wait for
+//    this wave's LDS writes (lds_barrier) instead of __syncthreads(), whose fence
+//    drains the transfers.
+// 2. The column operand is loaded 16 bytes per lane (8 columns of one rank index) and
+//    transposed across lanes in registers, instead of 4 bytes per lane in the layout
+//    the MFMA wants.  The vector L1 of a CU delivers 64 B per cycle to 16-byte loads
+//    but only 32 B per cycle to 4- and 8-byte loads (measured), and at these ranks the
+//    column operands are two to four times the bytes of the W tile.
+// The row operands are k-step pieces of 64 x 16 (2 KB each): up to eight are resident
+// (48 KB of LDS with the W tile: three workgroups per CU); with 16 k-steps the later
+// pieces wait in registers (all requested before W) and take the slot of a consumed
+// one behind a barrier.  Shorter contractions are faster in switch_gemm_kernel: there
+// the W tile is the only thing worth waiting for, and it is requested first.
+#pragma once
+#include "switch_gemm.hpp"
+
+namespace adafuse {
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+// This wave's LDS writes are done, then the workgroup meets.  A compiler barrier for
+// memory accesses as well, but no wait for outstanding global or global->LDS loads.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// 4 x 4 transpose of 32-bit values across the four lanes {t, t + 8, t + 16, t + 24} of each
+// half-wave: lane a of a group ends up with r[i] = what lane i held in r[a].  Lanes 16 apart
+// exchange through the row-swap instruction (one instruction swaps a register pair for both
+// partners), lanes 8 apart through a rotation by 8 inside their row of 16, written only into
+// the 8 lanes that take the partner's value (bank mask).
+__device__ __forceinline__ void transpose_lanes_8_16(uint32_t (&r)[4])
+{
+    typedef __attribute__((ext_vector_type(2))) unsigned int pair_t;
+    const pair_t s02 = __builtin_amdgcn_permlane16_swap(r[0], r[2], false, false);
+    const pair_t s13 = __builtin_amdgcn_permlane16_swap(r[1], r[3], false, false);
+    const uint32_t a0 = s02[0], a2 = s02[1], a1 = s13[0], a3 = s13[1];
+    constexpr int kRowRor8 = 0x128;
+    r[1] = __builtin_amdgcn_update_dpp(a1, a0, kRowRor8, 0xf, 0x3, false);  // lanes 0..7 of a row: the partner's r[0]
+    r[0] = __builtin_amdgcn_update_dpp(a0, a1, kRowRor8, 0xf, 0xc, false);  // lanes 8..15: the partner's r[1]
+    r[3] = __builtin_amdgcn_update_dpp(a3, a2, kRowRor8, 0xf, 0x3, false);
+    r[2] = __builtin_amdgcn_update_dpp(a2, a3, kRowRor8, 0xf, 0xc, false);
+}
+
+// Epilogue for the column assignment of this kernel (see fetch_x there): MFMA column index
+// m = 8 g + 4 h + i of a lane stands for the column pair 16 h + 4 i + g of the wave's 64
+// columns, so accumulator cb, v = 4 g + i is column 32 h + 8 i + 2 g + cb: per i one
+// 16-byte piece of the W tile again.  W' = rn_bf16(W + c * acc), W added last.
+template <int TC>
+__device__ __forceinline__ void w_tile_update_grouped(uint16_t (*s_w)[TC], const float16_t (&acc)[2][2], float c, int lcol0, int n, int h)
+{
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint4_t *slot = w_slot<TC>(s_w, 32 * rb + n, lcol0 / 8 + 4 * h + i);
+            const uint4_t wv = *slot;
+            float o[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) o[q] = c * acc[rb][q & 1][4 * (q >> 1) + i];
+            uint4_t out;
+#pragma unroll
+            for (int hh = 0; hh < 4; ++hh)
+                out[hh] = pack_bf16_rne(o[2 * hh] + bf16_lo(wv[hh]), o[2 * hh + 1] + bf16_hi(wv[hh]));
+            *slot = out;
+        }
+}
+
+template <int R, int NT, int NW>
+__global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchParams p)
+{
+    static_assert(R % 16 == 0, "whole k-steps");
+    constexpr int KS = R / 16;      // k-steps per expert
+    constexpr int STEPS = NT * KS;  // k-steps per tile
+    static_assert(STEPS >= 1 && STEPS <= 16, "1 to 16 k-steps");
+    constexpr int NS = STEPS <= 8 ? STEPS : 8;  // row-operand pieces resident in LDS; further ones wait in registers for a slot
+    // Column-operand k-steps requested before W (8 loads and 8 registers each): all of
+    // them, as long as the wave stays within the 63 outstanding loads its counter can
+    // hold (beyond that the W requests themselves would stall); the rest is requested
+    // as slots are consumed and lands behind W.
+    constexpr int XD = STEPS <= 8 ? STEPS : 6;
+    constexpr int NTHR = 64 * NW;
+    constexpr int TR = kGemmTileRows, TC = kGemmWaveCols * NW;
+    constexpr int WQ = TR * TC / 8 / NTHR;
+    static_assert(STEPS + 2 * XD + WQ <= 63, "outstanding loads");
+    constexpr int BB = TR * 32 / NTHR;  // bytes of one k-step of the row operand (64 rows x 32 B) per thread
+    static_assert(BB == 8 || BB == 4, "4 or 8 waves");
+    using BPiece = typename std::conditional<BB == 8, uint2_t, uint32_t>::type;
+
+    __shared__ __align__(16) uint16_t s_b[NS][TR][16];
+    __shared__ __align__(16) uint16_t s_w[TR][TC];  // pieces permuted: w_slot
+
+    Terms terms;
+    if (!load_terms<NT>(p, terms)) return;
+    const int nt = p.inplace ? (p.mode == 2 ? 2 * p.k : p.k) : p.k;
+
+    const TileDev tile = p.tiles[blockIdx.x];
+    const MatDev m = p.mats[tile.mat];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wc = tid >> 6;
+    const int n = lane & 31;
+    const int h = lane >> 5;
+    const int lcol0 = 64 * wc;
+    const int rows_left = tile.rows_left, cols_left = tile.cols_left;
+
+    // operand addressing as in the ring kernel: one descriptor per k-step, one offset
+    // register per lane; a k-step of an expert that is not in use gets an empty
+    // descriptor (zeros without a memory access), so all of this is straight-line code
+    // Column operand: 16-byte loads (8 columns of one rank index; twice the bytes per L1
+    // cycle of 4-byte loads, and the L1 is what this kernel keeps busiest).  Lane n = t + 8 a
+    // (t < 8, a < 4) loads the wave's columns 8 t .. 8 t + 7 at rank indices 8 h + a and
+    // 8 h + 4 + a of a k-step; a transpose across a then leaves it with the column pair
+    // 4 t + a at the 8 rank indices 8 h .. 8 h + 7, which is what its MFMA operands hold.
+    int acol = lcol0 + 8 * (n & 7);
+    acol = tile.col0 + (acol < cols_left ? acol : cols_left - 8);
+    const uint32_t in_bytes = 2u * (uint32_t)m.in;
+    const uint32_t xoff = (uint32_t)(8 * h + (n >> 3)) * in_bytes + 2u * (uint32_t)acol;
+    constexpr int BPR = 32 / BB;  // threads per row of the piece
+    const int brow = tid / BPR < rows_left ? tid / BPR : rows_left - 1;
+    const uint32_t boff = 2u * (uint32_t)brow * R + (uint32_t)BB * (tid % BPR);
+    const uint32_t b_bytes = (uint32_t)(m.out - tile.row0) * R * 2u;
+    auto in_use = [&](int step) { return step / KS < nt && terms.c[step / KS] != 0.0f; };
+    auto fetch_b = [&](BPiece &v, int step) {
+        const __amdgpu_buffer_rsrc_t rs =
+            make_buffer(m.b_bank + ((size_t)terms.e[step / KS] * m.out + tile.row0) * R, in_use(step) ? b_bytes : 0u);
+        if constexpr (BB == 8)
+            v = ld_buffer_b64(rs, boff, 32u * (step % KS));
+        else
+            v = ld_buffer_b32(rs, boff, 32u * (step % KS));
+    };
+    auto fetch_x = [&](uint4_t (&d)[2], int step) {
+        const __amdgpu_buffer_rsrc_t rs = make_buffer(m.a_bank + ((size_t)terms.e[step / KS] * R + 16 * (step % KS)) * m.in,
+                                                      in_use(step) ? 16u * in_bytes : 0u);
+        d[0] = ld_buffer_b128(rs, xoff, 0u);
+        d[1] = ld_buffer_b128(rs, xoff, 4u * in_bytes);
+    };
+
+    // ---- requests: operands first, the W tile last
+    BPiece vb[STEPS];
+    uint4_t xq[XD][2];
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) fetch_b(vb[s], s);
+#pragma unroll
+    for (int s = 0; s < XD; ++s) fetch_x(xq[s], s);
+    __builtin_amdgcn_sched_barrier(0);
+    // W: wave w's instruction i fills the 1 KB of LDS that starts at piece slot 64 (w + NW i);
+    // lane l delivers slot 64 (w + NW i) + l, i.e. the piece of the row that w_slot puts there.
+    // Rows and columns beyond the matrix edge are clamped to valid ones and never stored.
+    {
+        const __amdgpu_buffer_rsrc_t rs = make_buffer(tile.w_src, 0xffffffffu);
+#pragma unroll
+        for (int i = 0; i < WQ; ++i) {
+            const int q = 64 * (wc + NW * i) + lane;
+            const int row = q / (TC / 8), pc = (q % (TC / 8)) ^ (row & 31);
+            const int cr = row < rows_left ? row : rows_left - 1;
+            const int cc = 8 * pc < cols_left ? 8 * pc : cols_left - 8;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t *)(&s_w[0][0] + 512 * (wc + NW * i)), 16,
+                                                     (int)(2u * ((uint32_t)cr * (uint32_t)tile.ldw + (uint32_t)cc)), 0, 0, 2 /* non-temporal */);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- row operands into LDS, visible to the workgroup without waiting for W
+    auto stash_b = [&](const BPiece &v, int slot) {
+        *reinterpret_cast<BPiece *>(&s_b[slot][tid / BPR][(BB / 2) * (tid % BPR)]) = v;
+    };
+#pragma unroll
+    for (int s = 0; s < NS; ++s) stash_b(vb[s], s);
+    lds_barrier();
+
+    float16_t acc[2][2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.0f;
+
+    // ---- the contraction, while the W tile lands
+    float c_last = 0.0f;
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+        if (s % KS == 0 && in_use(s)) {  // a new expert: rescale what is accumulated so far (uniform branch, no loads inside)
+            const float c = terms.c[s / KS];
+            if (c_last != 0.0f) {
+                const float ratio = c_last / c;
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[rb][cb][v] *= ratio;
+            }
+            c_last = c;
+        }
+        uint32_t d[8];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            uint32_t r[4] = {xq[s % XD][j][0], xq[s % XD][j][1], xq[s % XD][j][2], xq[s % XD][j][3]};
+            transpose_lanes_8_16(r);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) d[4 * j + i] = r[i];
+        }
+        const uint4_t xe = {__builtin_amdgcn_perm(d[1], d[0], 0x05040100u), __builtin_amdgcn_perm(d[3], d[2], 0x05040100u),
+                            __builtin_amdgcn_perm(d[5], d[4], 0x05040100u), __builtin_amdgcn_perm(d[7], d[6], 0x05040100u)};
+        const uint4_t xo = {__builtin_amdgcn_perm(d[1], d[0], 0x07060302u), __builtin_amdgcn_perm(d[3], d[2], 0x07060302u),
+                            __builtin_amdgcn_perm(d[5], d[4], 0x07060302u), __builtin_amdgcn_perm(d[7], d[6], 0x07060302u)};
+        const bf16x8_t x0 = __builtin_bit_cast(bf16x8_t, xe), x1 = __builtin_bit_cast(bf16x8_t, xo);
+        if (s + XD < STEPS) fetch_x(xq[s % XD], s + XD);  // the slot is consumed: refill it
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            const uint4_t y = *reinterpret_cast<const uint4_t *>(&s_b[s % NS][32 * rb + n][8 * h]);
+            const bf16x8_t yy = __builtin_bit_cast(bf16x8_t, y);
+            acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0, yy, acc[rb][0], 0, 0, 0);
+            acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1, yy, acc[rb][1], 0, 0, 0);
+        }
+        if (s + NS < STEPS) {  // the ring turns: k-step s + NS takes this slot
+            lds_barrier();     // every wave is done reading it
+            stash_b(vb[s + NS], s % NS);
+            // the refill is visible to its readers through the barrier of the next
+            // k-step, or, when no further slot turns, through this one
+            if (s + 1 + NS >= STEPS) lds_barrier();
+        }
+    }
+
+    // ---- the W tile has to be there now: the fence of this barrier waits for every wave's transfers
+    __syncthreads();
+    if (c_last != 0.0f) w_tile_update_grouped<TC>(s_w, acc, c_last, lcol0, n, h);
+    __syncthreads();
+    w_tile_store<TC, NTHR, WQ>(s_w, tile, opaque_copy(tid));
+}
+
+}  // namespace adafuse

@@ -290,7 +290,8 @@ def test_one_full_layer_of_the_7b_shape(oracle, kernel):
     m.close()
 
 
-@pytest.mark.parametrize("name", ["llama2_7b_attn", "llama2_7b_all", "llama3_8b_gqa_all", "llama2_13b_all"])
+@pytest.mark.parametrize("name", ["llama2_7b_attn", "llama2_7b_all", "llama3_8b_gqa_all", "llama2_13b_all",
+                                  "llama2_7b_all_r64", "llama2_7b_all_r128"])
 def test_full_size_models_sampled_rows(oracle, name):
     """The full model in the launch configuration the bench times (all layers, one
     launch per token, library's kernel choice): sampled rows of EVERY matrix at
@@ -599,11 +600,13 @@ def test_per_matrix_launches_give_the_same_bits(oracle):
 
 @pytest.mark.parametrize("r,k,inplace", [(64, 2, False), (128, 2, False), (64, 2, True), (16, 4, False), (32, 1, True),
                                          (32, 4, False), (64, 4, False), (32, 2, True), (32, 3, False), (16, 3, False),
-                                         (16, 4, True), (8, 4, True), (128, 4, False), (64, 3, True), (16, 3, True)])
+                                         (16, 4, True), (8, 4, True), (128, 4, False), (64, 3, True), (16, 3, True),
+                                         (128, 1, False), (32, 4, True), (32, 2, False)])
 def test_rank_looped_kernel_modes(oracle, r, k, inplace):
-    """The rank-looped kernels in all their forms -- unrolled (1, 2 or 4 terms), the k-step ring
-    (4 terms at ranks 32 and 64, 8 terms at rank 16, also with terms left unused: k = 3) and
-    the run-time expert loop (8 terms at other ranks, or 4 at rank 128): MERGE / SWAP / UNMERGE, out of place and in place, two
+    """The rank-looped kernels in all their forms -- unrolled (up to 7 k-steps of 16 rank indices per
+    tile), overlapped with the W fetch (8 to 16 k-steps: e.g. top-2 at ranks 64 and 128, 4 terms at
+    ranks 32 and 64, 8 terms at ranks 16 and 32, also with terms left unused: k = 3) and the
+    run-time expert loop (the rest): MERGE / SWAP / UNMERGE, out of place and in place, two
     ragged matrices."""
     dev = torch.device("cuda:0")
     g = torch.Generator().manual_seed(r * 10 + k)
