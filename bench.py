@@ -226,7 +226,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": read_traffic(wl.name, kernel_name) if mode == af.SWAP and not args.inplace else None,
-                     "kernel": f"switch_{kernel_name}_kernel" if mode == af.SWAP else "switch_copy_kernel",
+                     "kernel": ctx.switch_kernel_name(wl.k, mode),
                      "algorithmic_bytes_per_launch": alg_bytes, "early_out_launches_excluded": early_outs,
                      "kernel_us": {"mean": avg_kernel_s * 1e6, "median": srt[len(srt) // 2] * 1e3,
                                    "p95": srt[int(0.95 * (len(srt) - 1))] * 1e3, "min": srt[0] * 1e3}},

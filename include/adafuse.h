@@ -128,6 +128,13 @@ adafuse_status adafuse_set_kernel(adafuse_ctx *ctx, int32_t kernel);
 /* Fill *info (HOST) with the context's geometry. */
 adafuse_status adafuse_get_info(const adafuse_ctx *ctx, adafuse_info *info);
 
+/* Name of the device function that adafuse_fused_switch(ctx, ..., k, ..., mode, ...)
+ * would launch (without template arguments, as a kernel trace shows it), for
+ * labelling measurements: the form of the default kernel depends on rank and
+ * term count.  A static string; NULL for a NULL context or arguments that the
+ * switch would refuse. */
+const char *adafuse_switch_kernel_name(const adafuse_ctx *ctx, int32_t k, int32_t mode);
+
 /*
  * Pre-gating router for T tokens (Eq.1's G applied to x^1, Eq.2):
  *   logits[t][e] = sum_i hidden[t][i] * w_router[e][i]      (fp32 result)

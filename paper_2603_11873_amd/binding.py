@@ -12,7 +12,7 @@ KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_GEMM = 0, 1, 2, 3
 
 EXPORTS = ["adafuse_create", "adafuse_destroy", "adafuse_set_kernel", "adafuse_get_info",
            "adafuse_pregate", "adafuse_fused_switch", "adafuse_switch_per_matrix", "adafuse_forward_merged", "adafuse_forward_dynamic",
-           "adafuse_status_string"]
+           "adafuse_switch_kernel_name", "adafuse_status_string"]
 
 
 class AdafuseError(RuntimeError):
@@ -67,6 +67,8 @@ def load_library():
     L.adafuse_forward_merged.argtypes = [vp, vp, vp, vp]
     L.adafuse_forward_dynamic.restype = i32
     L.adafuse_forward_dynamic.argtypes = [vp, C.POINTER(i32), C.POINTER(f32), i32, f32, vp, vp, vp, vp]
+    L.adafuse_switch_kernel_name.restype = C.c_char_p
+    L.adafuse_switch_kernel_name.argtypes = [vp, i32, i32]
     L.adafuse_status_string.restype = C.c_char_p
     L.adafuse_status_string.argtypes = [i32]
     _lib = L
@@ -151,6 +153,11 @@ class Context:
         if st != 0:
             raise AdafuseError(st, "adafuse_get_info")
         return info
+
+    def switch_kernel_name(self, k, mode):
+        """adafuse_switch_kernel_name: the device function a switch with these arguments launches, or None."""
+        name = load_library().adafuse_switch_kernel_name(self._h, k, mode)
+        return None if name is None else name.decode()
 
     def fused_switch(self, idx_prev, gates_prev, idx_next, gates_next, k, scale, mode, stream=None):
         """adafuse_fused_switch; idx/gates are device tensors (int32[k] / fp32[k]) or None."""

@@ -129,32 +129,48 @@ bool launch_mfma_any(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t
     }
 }
 
-// Which form runs (R, terms): the unrolled kernel up to 7 k-steps of 16 rank indices per
-// tile, the overlapped one (W straight into LDS, contraction meanwhile) for 8 to 16, the
-// run-time expert loop beyond.  Measurement knob ADAFUSE_GEMM_FORM: 1 = never the
-// overlapped form, 2 = the expert loop for every launch with 4 or more terms.
+// Which form of the rank-looped kernel runs (rank, term bucket): the unrolled kernel up to
+// 7 k-steps of 16 rank indices per tile, the overlapped one (W straight into LDS,
+// contraction meanwhile) for 8 to 16, the run-time expert loop beyond.  Measurement knob
+// ADAFUSE_GEMM_FORM: 1 = never the overlapped form, 2 = the expert loop for every launch
+// with 4 or more terms, 3 = the overlapped form for short contractions too.
+enum GemmForm { kFormUnrolled, kFormOverlap, kFormLoop };
+
+GemmForm pick_gemm_form(int r, int nt)
+{
+    static const int knob = [] { const char *e = std::getenv("ADAFUSE_GEMM_FORM"); return e ? std::atoi(e) : 0; }();
+    const int steps = nt * ((r + 15) / 16);
+    const bool can_overlap = r % 16 == 0 && steps <= 16;
+    const bool can_unroll = nt <= 2 || (nt == 4 && r <= 16);  // every row operand fits beside the W tile
+    const bool force_loop = knob == 2 && nt >= 4;
+    if (can_overlap && (steps >= 8 || knob == 3) && knob != 1 && !force_loop) return kFormOverlap;
+    if (can_unroll && !force_loop) return kFormUnrolled;
+    return kFormLoop;
+}
+
 template <int R, int NT, int NW>
 bool launch_gemm_form(const SwitchParams &p, int64_t n_tiles, hipStream_t s)
 {
     const dim3 grid((unsigned)n_tiles), block(64 * NW);
-    static const int form = [] { const char *e = std::getenv("ADAFUSE_GEMM_FORM"); return e ? std::atoi(e) : 0; }();
-    constexpr int steps = NT * ((R + 15) / 16);
-    constexpr bool can_unroll = NT <= 2 || (NT == 4 && R <= 16);  // every row operand fits beside the W tile
-    if constexpr (R % 16 == 0 && steps <= 16) {
-        if ((steps >= 8 || form == 3) && form != 1 && !(form == 2 && NT >= 4)) {
+    switch (pick_gemm_form(R, NT)) {
+    case kFormOverlap:
+        if constexpr (R % 16 == 0 && NT * ((R + 15) / 16) <= 16) {
             hipLaunchKernelGGL((switch_gemm_overlap_kernel<R, NT, NW>), grid, block, 0, s, p);
             return true;
         }
-    }
-    if constexpr (can_unroll) {
-        if (!(form == 2 && NT >= 4)) {
+        break;
+    case kFormUnrolled:
+        if constexpr (NT <= 2 || (NT == 4 && R <= 16)) {
             hipLaunchKernelGGL((switch_gemm_kernel<R, NT, NW>), grid, block, 0, s, p);
             return true;
         }
-    }
-    if constexpr (NT >= 4) {
-        hipLaunchKernelGGL((switch_gemm_loop_kernel<R, NW>), grid, block, 0, s, p);
-        return true;
+        break;
+    case kFormLoop:
+        if constexpr (NT >= 4) {
+            hipLaunchKernelGGL((switch_gemm_loop_kernel<R, NW>), grid, block, 0, s, p);
+            return true;
+        }
+        break;
     }
     return false;
 }
@@ -556,6 +572,27 @@ adafuse_status adafuse_forward_dynamic(adafuse_ctx *ctx, const int32_t *idx_host
         y += m.out;
     }
     return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
+}
+
+const char *adafuse_switch_kernel_name(const adafuse_ctx *ctx, int32_t k, int32_t mode)
+{
+    if (!ctx) return nullptr;
+    if (mode != ADAFUSE_MERGE && mode != ADAFUSE_UNMERGE && mode != ADAFUSE_SWAP) return nullptr;
+    const bool need_next = mode != ADAFUSE_UNMERGE;
+    const bool need_prev = ctx->inplace && mode != ADAFUSE_MERGE;
+    if ((need_next || need_prev) && (k < 1 || k > ctx->k_max)) return nullptr;
+    const bool copy_only = !ctx->inplace && mode == ADAFUSE_UNMERGE;
+    const int n_terms = (need_prev ? k : 0) + (need_next ? k : 0);
+    switch (ctx->kernel) {
+    case ADAFUSE_KERNEL_MFMA: return copy_only ? "switch_copy_kernel" : "switch_mfma_kernel";
+    case ADAFUSE_KERNEL_GEMM:
+        switch (pick_gemm_form(ctx->r, terms_bucket(n_terms > 0 ? n_terms : 1))) {
+        case kFormOverlap: return "switch_gemm_overlap_kernel";
+        case kFormUnrolled: return "switch_gemm_kernel";
+        default: return "switch_gemm_loop_kernel";
+        }
+    default: return "switch_valu_kernel";
+    }
 }
 
 const char *adafuse_status_string(int32_t status)

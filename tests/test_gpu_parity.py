@@ -660,6 +660,30 @@ def test_rank_looped_kernel_modes(oracle, r, k, inplace):
     ctx.close()
 
 
+@pytest.mark.parametrize("r,k,inplace,mode,expect", [
+    (8, 2, False, "SWAP", "switch_gemm_kernel"), (16, 4, False, "SWAP", "switch_gemm_kernel"),
+    (64, 2, False, "SWAP", "switch_gemm_overlap_kernel"), (128, 2, False, "MERGE", "switch_gemm_overlap_kernel"),
+    (32, 2, True, "SWAP", "switch_gemm_overlap_kernel"), (32, 2, True, "MERGE", "switch_gemm_kernel"),
+    (128, 4, False, "SWAP", "switch_gemm_loop_kernel"), (64, 2, False, "UNMERGE", "switch_gemm_kernel"),
+])
+def test_switch_kernel_name_follows_the_dispatch(r, k, inplace, mode, expect):
+    """The label measurements use for a launch is the form the library would run: by the
+    number of k-steps of 16 rank indices per tile (terms rounded up to 1, 2, 4 or 8)."""
+    if os.environ.get("ADAFUSE_GEMM_FORM"):
+        pytest.skip("a forced kernel form changes the dispatch")
+    dev = torch.device("cuda:0")
+    wb = torch.zeros((64, 256), dtype=torch.bfloat16, device=dev)
+    a = torch.zeros((4, r, 256), dtype=torch.bfloat16, device=dev)
+    b = torch.zeros((4, 64, r), dtype=torch.bfloat16, device=dev)
+    ctx = af.Context([(wb, wb if inplace else torch.zeros_like(wb), a, b)], k)
+    assert ctx.switch_kernel_name(k, getattr(af, mode)) == expect
+    assert ctx.switch_kernel_name(k + 1, af.SWAP) is None      # more terms than the context allows
+    assert ctx.switch_kernel_name(k, 7) is None                 # no such mode
+    ctx.set_kernel(af.KERNEL_VALU)
+    assert ctx.switch_kernel_name(k, af.SWAP) == "switch_valu_kernel"
+    ctx.close()
+
+
 # ---- the step after the switch: merged GEMV versus the un-merged dynamic-adapter path -------
 
 @pytest.mark.parametrize("name,layers", [("toy", 2), ("llama2_7b_all", 1)])
