@@ -25,6 +25,13 @@
  * returns a framework type.  All functions return an adafuse_status; none
  * throws, aborts or prints.  Argument checks that need no GPU run before any
  * HIP call, so invalid arguments are reported on a machine without a GPU too.
+ *
+ * Threads: a context is not locked.  Calls that only enqueue (pregate, the
+ * switches, the forward passes, get_info, switch_kernel_name) may run from
+ * several host threads at once; adafuse_set_kernel and adafuse_destroy must not
+ * overlap with any other call on the same context.  Two switches on the same
+ * context write the same W_work: order them on one stream (or with events)
+ * like any other pair of kernels that write the same memory.
  */
 #ifndef ADAFUSE_H
 #define ADAFUSE_H
