@@ -524,11 +524,14 @@ def test_inplace_needs_prev_and_rejects_large_k():
     ctx.close()
 
 
-def test_inplace_full_layer_7b_shape(oracle):
-    """In-place SWAP on one Llama-2-7B-shaped layer (4 terms of rank 8 per element), checked on
-    sampled rows.  The state before the step is an oracle merge of token 0 placed into those rows
-    (the other rows hold the base weights; every row is switched, the sampled ones are compared)."""
-    wl = wlmod.scaled_down(wlmod.WORKLOADS["llama2_7b_all"], 1)
+@pytest.mark.parametrize("name", ["llama2_7b_all", "llama3_8b_gqa_all", "llama2_7b_all_r64"])
+def test_inplace_full_layer(oracle, name):
+    """In-place SWAP on one full-size layer (4 terms of rank 8; 8 terms of rank 16; 4 terms of rank
+    64 -- the last two through the kernel form that overlaps the contraction with the W fetch),
+    checked on sampled rows.  The state before the step is an oracle merge of token 0 placed into
+    those rows (the other rows hold the base weights; every row is switched, the sampled ones are
+    compared)."""
+    wl = wlmod.scaled_down(wlmod.WORKLOADS[name], 1)
     dev = torch.device("cuda:0")
     mats = []
     for mi in range(len(wl.mats)):
