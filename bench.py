@@ -21,6 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense
 
 
 def parse_args():
@@ -203,6 +204,8 @@ def main():
     if args.inplace:   # the previous token's slices are read too
         alg_bytes += wl.algorithmic_bytes - 4 * wl.elements
     achieved = alg_bytes / avg_kernel_s / 1e9
+    # the second bound: 2 k r flops per element of the low-rank product (twice that in place), against the dense bf16 MFMA peak
+    alg_flops = 0 if mode != af.SWAP and not args.inplace else wl.flops * (2 if args.inplace and mode == af.SWAP else 1)
     srt = sorted(kernel_ms)
 
     out = {
@@ -228,6 +231,9 @@ def main():
                      "traffic": read_traffic(wl.name, kernel_name) if mode == af.SWAP and not args.inplace else None,
                      "kernel": ctx.switch_kernel_name(wl.k, mode),
                      "algorithmic_bytes_per_launch": alg_bytes, "early_out_launches_excluded": early_outs,
+                     "matrix_core": {"achieved": alg_flops / avg_kernel_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                     "frac": alg_flops / avg_kernel_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                                     "algorithmic_flops_per_launch": alg_flops},
                      "kernel_us": {"mean": avg_kernel_s * 1e6, "median": srt[len(srt) // 2] * 1e3,
                                    "p95": srt[int(0.95 * (len(srt) - 1))] * 1e3, "min": srt[0] * 1e3}},
     }
