@@ -221,32 +221,42 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
     // of a group, the rest of the address uniform.  (Shapes are limited to 2^22
     // in either direction: a slice stays below 2^31 bytes.)
     const uint32_t b_bytes = (uint32_t)(m.out - tile.row0) * R * 2u;  // from the tile's first row to the end of the expert
-    auto fetch_b = [&](uint4_t (&v)[BQ], int e) {
-        const __amdgpu_buffer_rsrc_t rs = make_buffer(m.b_bank + ((size_t)e * m.out + tile.row0) * R, b_bytes);
+    // Up to rank 16 a slice is one k-step per row: 64 rows of 32 bytes in LDS, of which the
+    // first 2 R hold data.  EVERY thread brings the same number of dwords of that image
+    // (dword d = row d / 8, position d % 8), the positions beyond the rank through an offset
+    // outside the descriptor, which reads as zero: no load and no store sits in a branch
+    // (the compiler ends a conditional block that loads with a wait for all loads, which
+    // made the four experts' slices four round trips in a row).  From rank 32 on the
+    // 16-byte pieces of a slice divide evenly among the threads.
+    using BReg = typename std::conditional<(R <= 16), uint32_t, uint4_t>::type;
+    constexpr int BN = R <= 16 ? TR * 8 / NTHR : BQ;  // registers of that type per thread and slice
+    static_assert((TR * 8) % NTHR == 0, "the dwords of a one-k-step slice divide evenly among the threads");
+    constexpr bool kAllThreads = R <= 16 || BV % NTHR == 0;  // else (rank 32 with 8 waves) the last pieces are guarded
+    auto fetch_b = [&](BReg (&v)[BN], int e, bool used) {
+        const __amdgpu_buffer_rsrc_t rs = make_buffer(m.b_bank + ((size_t)e * m.out + tile.row0) * R, used ? b_bytes : 0u);
 #pragma unroll
-        for (int i = 0; i < BQ; ++i) {
+        for (int i = 0; i < BN; ++i) {
             const int q = tid + NTHR * i;
-            const int row = q / (RP / 8), piece = q % (RP / 8);
-            const int cr = row < rows_left ? row : rows_left - 1;
-            if (q < BV) {
-                if constexpr (R >= 8) {
-                    v[i] = ld_buffer_b128(rs, 2u * ((uint32_t)cr * R + 8u * piece), 0u);
-                } else {  // rank 4: a row is 8 bytes
-                    const uint2_t t = ld_buffer_b64(rs, 2u * (uint32_t)cr * R, 0u);
-                    v[i] = uint4_t{t[0], t[1], 0u, 0u};
-                }
+            if constexpr (R <= 16) {
+                const int row = q / 8, pos = q % 8;
+                const int cr = row < rows_left ? row : rows_left - 1;
+                v[i] = ld_buffer_b32(rs, 2 * pos < R ? 2u * (uint32_t)cr * R + 4u * pos : 0xffffff00u, 0u);
+            } else {
+                const int row = q / (R / 8), piece = q % (R / 8);
+                const int cr = row < rows_left ? row : rows_left - 1;
+                if (kAllThreads || q < BV) v[i] = ld_buffer_b128(rs, 2u * ((uint32_t)cr * R + 8u * piece), 0u);
             }
         }
     };
-    auto stash_b = [&](const uint4_t (&v)[BQ], int slot) {
+    auto stash_b = [&](const BReg (&v)[BN], int slot) {
 #pragma unroll
-        for (int i = 0; i < BQ; ++i) {
+        for (int i = 0; i < BN; ++i) {
             const int q = tid + NTHR * i;
-            const int row = q / (RP / 8), piece = q % (RP / 8);
-            if (q < BV) {
-                *reinterpret_cast<uint4_t *>(&s_b[slot][row][8 * P::b_piece(row, piece)]) = v[i];
-                if constexpr (kPadded)  // second half of the single k-step: zeros
-                    *reinterpret_cast<uint4_t *>(&s_b[slot][row][8]) = uint4_t{0u, 0u, 0u, 0u};
+            if constexpr (R <= 16) {
+                reinterpret_cast<uint32_t *>(&s_b[slot][0][0])[q] = v[i];
+            } else {
+                const int row = q / (R / 8), piece = q % (R / 8);
+                if (kAllThreads || q < BV) *reinterpret_cast<uint4_t *>(&s_b[slot][row][8 * P::b_piece(row, piece)]) = v[i];
             }
         }
     };
@@ -271,10 +281,9 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
             }
     };
 
-    uint4_t vb[NB][BQ];
+    BReg vb[NB][BN];
 #pragma unroll
-    for (int j = 0; j < NB; ++j)
-        if (j < nt) fetch_b(vb[j], terms.e[j]);
+    for (int j = 0; j < NB; ++j) fetch_b(vb[j], terms.e[j], j < nt);  // an unused term: empty descriptor, zeros
     XChunk xq[QX];
 #pragma unroll
     for (int i = 0; i < QX; ++i)
@@ -282,16 +291,14 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
     if constexpr (kOperandsFirst) {
         w_tile_request<TC, NTHR>(wreg, tile, tid);
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
-            if (j < nt) stash_b(vb[j], j);
+        for (int j = 0; j < NB; ++j) stash_b(vb[j], j);
     }
 
     // W tile and row operands into LDS as they land: the registers are free for the contraction
     w_tile_park<TC, NTHR>(s_w, wreg, tid);
     if constexpr (!kOperandsFirst) {
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
-            if (j < nt) stash_b(vb[j], j);
+        for (int j = 0; j < NB; ++j) stash_b(vb[j], j);
     }
     __syncthreads();
 
@@ -309,9 +316,9 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
     for (int j = 0; j < NT; ++j) {
         const float c = terms.c[j];
         const bool active = j < nt && c != 0.0f;  // uniform; a zero coefficient contributes nothing
-        uint4_t vroll[BQ];
+        BReg vroll[BN];
         if constexpr (NT > NB) {
-            if (j + NB < NT && j + NB < nt) fetch_b(vroll, terms.e[j + NB]);  // rolls into this expert's slot below
+            if (j + NB < NT) fetch_b(vroll, terms.e[j + NB], j + NB < nt);  // rolls into this expert's slot below
         }
         if (active && c_last != 0.0f) {
             const float ratio = c_last / c;
@@ -357,7 +364,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
         if constexpr (NT > NB) {
             if (j + NB < NT) {
                 __syncthreads();  // every wave is done reading this expert's slot ...
-                if (j + NB < nt) stash_b(vroll, j % NB);
+                stash_b(vroll, j % NB);
                 // ... and the refill is complete before expert j + NB reads it: the barrier
                 // after expert j + 1 (NB >= 2) orders it, or, for the last refill, this one
                 if (j + NB + 1 >= NT) __syncthreads();
