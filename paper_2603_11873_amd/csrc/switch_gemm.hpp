@@ -183,8 +183,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
     using P = GemmPlan<R, NT>;
     constexpr int NTHR = 64 * NW;
     constexpr int KCH = P::KCH, NCH = P::NCH, TOT = P::TOT, QX = P::QX, NB = P::NB;
-    constexpr int RP = P::RP, BP = P::BP, BV = P::BV, BQ = P::BQ(NTHR);
-    constexpr bool kPadded = P::kPadded;
+    constexpr int BP = P::BP, BV = P::BV, BQ = P::BQ(NTHR);
     constexpr int TR = kGemmTileRows, TC = kGemmWaveCols * NW;
     constexpr int WQ = TR * TC / 8 / NTHR;  // 16-byte pieces of the W tile per thread
 
@@ -204,7 +203,6 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
     const int h = lane >> 5;   // which half of the k-step / of a 16-column group
     const int lcol0 = 64 * wc;
     const int rows_left = tile.rows_left, cols_left = tile.cols_left;
-    const int ldw = tile.ldw;
 
     // ---- request everything.  Loads return in issue order, so operand loads (cache
     // hits) queued behind the W loads (HBM) sit on their return slots until W has
@@ -429,7 +427,6 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams 
     const int lrow0 = 64 * wr;                         // wave origin inside the tile
     const int lcol0 = 64 * wc;
     const int rows_left = tile.rows_left, cols_left = tile.cols_left;
-    const int ldw = tile.ldw;
 
     // ---- W first.  The 32x32 result layout gives a lane 16-byte pieces of 32
     // different rows, which streams badly; so the workgroup moves its W tile with
