@@ -89,11 +89,12 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
     constexpr int STEPS = NT * KS;  // k-steps per tile
     static_assert(STEPS >= 1 && STEPS <= 16, "1 to 16 k-steps");
     constexpr int NS = STEPS <= 8 ? STEPS : 8;  // row-operand pieces resident in LDS; further ones wait in registers for a slot
-    // Column-operand k-steps requested before W (8 loads and 8 registers each): all of
-    // them, as long as the wave stays within the 63 outstanding loads its counter can
-    // hold (beyond that the W requests themselves would stall); the rest is requested
-    // as slots are consumed and lands behind W.
-    constexpr int XD = STEPS <= 8 ? STEPS : 6;
+    // Column-operand k-steps requested before W (2 loads and 8 registers each): all of
+    // them up to 8 k-steps; with 16, as many as leave the kernel at 168 registers (three
+    // workgroups per CU: measured, all 16 with two workgroups is 8 % slower).  The rest is
+    // requested as slots are consumed and lands behind W.  In all, a wave must stay
+    // within the 63 outstanding loads its counter can hold, or the W requests would stall.
+    constexpr int XD = STEPS <= 8 ? STEPS : (NT >= 8 ? 6 : 7);
     constexpr int NTHR = 64 * NW;
     constexpr int TR = kGemmTileRows, TC = kGemmWaveCols * NW;
     constexpr int WQ = TR * TC / 8 / NTHR;
