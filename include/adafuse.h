@@ -117,7 +117,9 @@ typedef struct {
  * Errors: NULL mats/ctx or NULL pointer inside a descriptor -> ERR_NULL;
  * n_mats < 1, bad E/r/k_max, reserved != 0, in-place and out-of-place matrices
  * mixed -> ERR_ARG;
- * out < 1, in < 8, in % 8, ldw < in, ldw % 8 -> ERR_SHAPE; pointer not 16-byte
+ * out < 1, in < 8, in % 8, ldw < in, ldw % 8, out or in > 2^22, ldw > 2^24
+ * (the kernels address a tile and an expert's slice with 32-bit offsets)
+ * -> ERR_SHAPE; pointer not 16-byte
  * aligned -> ERR_ALIGN; HIP failure -> ERR_HIP (no context is returned).
  */
 adafuse_status adafuse_create(const adafuse_matrix_desc *mats, int32_t n_mats,

@@ -63,7 +63,8 @@ adafuse_status validate_mats(const adafuse_matrix_desc *mats, int32_t n_mats, in
         if (m.reserved != 0) return ADAFUSE_ERR_ARG;
         if ((m.w_base == m.w_work) != (mats[0].w_base == mats[0].w_work)) return ADAFUSE_ERR_ARG;  // all in place or none
         if (m.out < 1 || m.in < 8 || (m.in % 8) != 0 || m.ldw < m.in || (m.ldw % 8) != 0) return ADAFUSE_ERR_SHAPE;
-        if (m.out > (1 << 22) || m.in > (1 << 22)) return ADAFUSE_ERR_SHAPE;
+        // 32-bit offsets inside a tile (64 rows of ldw) and inside one expert's slice (rank x in, out x rank)
+        if (m.out > (1 << 22) || m.in > (1 << 22) || m.ldw > (1 << 24)) return ADAFUSE_ERR_SHAPE;
         if (!aligned16(m.w_base) || !aligned16(m.w_work) || !aligned16(m.a_bank) || !aligned16(m.b_bank))
             return ADAFUSE_ERR_ALIGN;
     }

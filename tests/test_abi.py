@@ -67,6 +67,8 @@ def test_create_rejects_bad_arguments(L):
     assert _create(L, [_desc(in_=100)])[0] == ERR_SHAPE
     assert _create(L, [_desc(in_=64, ldw=56)])[0] == ERR_SHAPE
     assert _create(L, [_desc(in_=64, ldw=68)])[0] == ERR_SHAPE
+    assert _create(L, [_desc(in_=64, ldw=(1 << 24) + 8)])[0] == ERR_SHAPE   # beyond the 32-bit offsets inside a tile
+    assert _create(L, [_desc(in_=(1 << 22) + 8, ldw=(1 << 22) + 8)])[0] == ERR_SHAPE
     assert _create(L, [_desc(wb=0x10008)])[0] == ERR_ALIGN
     assert _create(L, [_desc(a=0x30002)])[0] == ERR_ALIGN
     # second descriptor bad, first good
