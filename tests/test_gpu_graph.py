@@ -17,11 +17,17 @@ ULP_TOL = 1
 MAX_DIFF_FRACTION = 0.01
 
 
-@pytest.mark.parametrize("kernel", [af.KERNEL_GEMM, af.KERNEL_MFMA, af.KERNEL_VALU])
-def test_captured_decode_step_replays_correctly(oracle, kernel):
-    wl = wlmod.WORKLOADS["toy"]
+@pytest.mark.parametrize("kernel,rank", [(af.KERNEL_GEMM, 4), (af.KERNEL_MFMA, 4), (af.KERNEL_VALU, 4), (af.KERNEL_GEMM, 64)])
+def test_captured_decode_step_replays_correctly(oracle, kernel, rank):
+    """rank 4: the toy workload; rank 64: the same matrices with experts of the paper-typical rank, which the
+    default kernel runs in its overlapped form (W tile transferred straight into LDS)."""
+    toy = wlmod.WORKLOADS["toy"]
+    wl = toy if rank == toy.r else wlmod.Workload("toy_r64", toy.layers, toy.d, toy.mats, toy.E, rank, toy.k, toy.T, 9,
+                                                  toy.scale, toy.repeat_prob)
     m = DeviceModel(wl)
     m.ctx.set_kernel(kernel)
+    if rank == 64:
+        assert m.ctx.switch_kernel_name(wl.k, af.SWAP) == "switch_gemm_overlap_kernel"
     dev = m.hidden.device
     hidx, hg, _, _ = oracle_decisions(oracle, m.hidden, m.router, wl.k)
 
