@@ -256,6 +256,10 @@ def main():
         # the router alone, one token per launch (launch-latency bound: us only)
         out["pregate_us"] = timed_launches(
             torch, stream, lambda: af.pregate(hidden[0:1], router, wl.k, out=(idx[0:1], gates[0:1], None), stream=stream), 64)
+        # ... and the whole sequence's decisions in one launch (T workgroups); same values into the same buffers
+        out["pregate_us"]["all_tokens_one_launch"] = timed_launches(
+            torch, stream, lambda: af.pregate(hidden, router, wl.k, out=(idx, gates, None), stream=stream), 16)
+        out["pregate_us"]["tokens"] = T
     if wl.repeat_prob > 0 and mode == af.SWAP:
         # tokens that keep the previous token's expert set (fresh gates) vs tokens that change it
         hidx = idx.cpu().tolist()
