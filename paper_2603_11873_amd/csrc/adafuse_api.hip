@@ -132,7 +132,8 @@ bool launch_mfma_any(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t
 
 // Which form of the rank-looped kernel runs (rank, term bucket): the unrolled kernel up to
 // 7 k-steps of 16 rank indices per tile, the overlapped one (W straight into LDS,
-// contraction meanwhile) for 8 to 16, the run-time expert loop beyond.  Measurement knob
+// contraction meanwhile) from 8 on, the run-time expert loop for what neither takes
+// (8 terms at the zero-padded ranks 4 and 8).  Measurement knob
 // ADAFUSE_GEMM_FORM: 1 = never the overlapped form, 2 = the expert loop for every launch
 // with 4 or more terms, 3 = the overlapped form for short contractions too.
 enum GemmForm { kFormUnrolled, kFormOverlap, kFormLoop };
@@ -141,7 +142,7 @@ GemmForm pick_gemm_form(int r, int nt)
 {
     static const int knob = [] { const char *e = std::getenv("ADAFUSE_GEMM_FORM"); return e ? std::atoi(e) : 0; }();
     const int steps = nt * ((r + 15) / 16);
-    const bool can_overlap = r % 16 == 0 && steps <= 16;
+    const bool can_overlap = r % 16 == 0 && steps <= 64;
     const bool can_unroll = nt <= 2 || (nt == 4 && r <= 16);  // every row operand fits beside the W tile
     const bool force_loop = knob == 2 && nt >= 4;
     if (can_overlap && (steps >= 8 || knob == 3) && knob != 1 && !force_loop) return kFormOverlap;
@@ -155,7 +156,7 @@ bool launch_gemm_form(const SwitchParams &p, int64_t n_tiles, hipStream_t s)
     const dim3 grid((unsigned)n_tiles), block(64 * NW);
     switch (pick_gemm_form(R, NT)) {
     case kFormOverlap:
-        if constexpr (R % 16 == 0 && NT * ((R + 15) / 16) <= 16) {
+        if constexpr (R % 16 == 0 && NT * ((R + 15) / 16) <= 64) {
             hipLaunchKernelGGL((switch_gemm_overlap_kernel<R, NT, NW>), grid, block, 0, s, p);
             return true;
         }

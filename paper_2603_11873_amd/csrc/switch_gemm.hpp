@@ -37,10 +37,10 @@
 // LDS for the row operands.
 // Three forms, by the number of k-steps (16 rank indices of one expert) a tile
 // takes: switch_gemm_kernel<R, NT> below, fully unrolled with every row operand
-// resident, up to 7; switch_gemm_overlap_kernel<R, NT> (its own header) for 8 to
-// 16, where the contraction is long enough to be worth running while the W tile
-// is still on its way; switch_gemm_loop_kernel<R> for the rest: a run-time loop
-// over the experts.
+// resident, up to 7; switch_gemm_overlap_kernel<R, NT> (its own header) from 8
+// on, where the contraction is long enough to be worth running while the W tile
+// is still on its way; switch_gemm_loop_kernel<R> for the rest (8 terms at the
+// zero-padded ranks 4 and 8): a run-time loop over the experts.
 // Gates stay out of the bf16 operands.  Experts are chained in ONE accumulator:
 //   acc = P_0;  acc = acc * (c_0/c_1) + P_1;  ...;  W' = rn_bf16(W + c_last * acc)
 // which equals W + sum_j c_j P_j up to fp32 rounding of the ratios (terms with a

@@ -1,5 +1,5 @@
-// Fused switch, rank-looped form for long contractions (8 to 16 k-steps of 16 rank
-// indices per tile: top-2 at ranks 64 and 128, four terms at ranks 32 and 64, ...).
+// Fused switch, rank-looped form for long contractions (8 to 64 k-steps of 16 rank
+// indices per tile: top-2 at ranks 64 and 128, four terms at ranks 32 to 128, ...).
 // Same tile, same MFMA arrangement, same arithmetic and same write-back as
 // switch_gemm_kernel.  Two things differ.
 //
@@ -23,8 +23,10 @@
 // The row operands are k-step pieces of 64 x 16 (2 KB each): up to eight are resident
 // (48 KB of LDS with the W tile: three workgroups per CU); with 16 k-steps the later
 // pieces wait in registers (all requested before W) and take the slot of a consumed
-// one behind a barrier.  Shorter contractions are faster in switch_gemm_kernel: there
-// the W tile is the only thing worth waiting for, and it is requested first.
+// one behind a barrier.  More than 16 k-steps (up to 64: eight terms of rank 128) run
+// as further phases of 16 after the first.  Shorter contractions are faster in
+// switch_gemm_kernel: there the W tile is the only thing worth waiting for, and it is
+// requested first.
 #pragma once
 #include "switch_gemm.hpp"
 
@@ -87,18 +89,20 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
     static_assert(R % 16 == 0, "whole k-steps");
     constexpr int KS = R / 16;      // k-steps per expert
     constexpr int STEPS = NT * KS;  // k-steps per tile
-    static_assert(STEPS >= 1 && STEPS <= 16, "1 to 16 k-steps");
-    constexpr int NS = STEPS <= 8 ? STEPS : 8;  // row-operand pieces resident in LDS; further ones wait in registers for a slot
+    constexpr int SP = STEPS <= 16 ? STEPS : 16;  // k-steps per phase
+    constexpr int PH = STEPS / SP;                // phases
+    static_assert(STEPS >= 1 && STEPS <= 64 && STEPS % SP == 0, "1 to 16 k-steps, or 32, 48, 64");
+    constexpr int NS = SP <= 8 ? SP : 8;  // row-operand pieces resident in LDS; further ones of the phase wait in registers for a slot
     // Column-operand k-steps requested before W (2 loads and 8 registers each): all of
     // them up to 8 k-steps; with 16, as many as leave the kernel at 168 registers (three
     // workgroups per CU: measured, all 16 with two workgroups is 8 % slower).  The rest is
     // requested as slots are consumed and lands behind W.  In all, a wave must stay
     // within the 63 outstanding loads its counter can hold, or the W requests would stall.
-    constexpr int XD = STEPS <= 8 ? STEPS : (NT >= 8 ? 6 : 7);
+    constexpr int XD = SP <= 8 ? SP : (PH >= 4 ? 4 : (PH >= 2 || NT >= 8 ? 6 : 7));
     constexpr int NTHR = 64 * NW;
     constexpr int TR = kGemmTileRows, TC = kGemmWaveCols * NW;
     constexpr int WQ = TR * TC / 8 / NTHR;
-    static_assert(STEPS + 2 * XD + WQ <= 63, "outstanding loads");
+    static_assert(SP + 2 * XD + WQ <= 63, "outstanding loads");
     constexpr int BB = TR * 32 / NTHR;  // bytes of one k-step of the row operand (64 rows x 32 B) per thread
     static_assert(BB == 8 || BB == 4, "4 or 8 waves");
     using BPiece = typename std::conditional<BB == 8, uint2_t, uint32_t>::type;
@@ -152,38 +156,9 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
         d[1] = ld_buffer_b128(rs, xoff, 4u * in_bytes);
     };
 
-    // ---- requests: operands first, the W tile last
-    BPiece vb[STEPS];
-    uint4_t xq[XD][2];
-#pragma unroll
-    for (int s = 0; s < STEPS; ++s) fetch_b(vb[s], s);
-#pragma unroll
-    for (int s = 0; s < XD; ++s) fetch_x(xq[s], s);
-    __builtin_amdgcn_sched_barrier(0);
-    // W: wave w's instruction i fills the 1 KB of LDS that starts at piece slot 64 (w + NW i);
-    // lane l delivers slot 64 (w + NW i) + l, i.e. the piece of the row that w_slot puts there.
-    // Rows and columns beyond the matrix edge are clamped to valid ones and never stored.
-    {
-        const __amdgpu_buffer_rsrc_t rs = make_buffer(tile.w_src, 0xffffffffu);
-#pragma unroll
-        for (int i = 0; i < WQ; ++i) {
-            const int q = 64 * (wc + NW * i) + lane;
-            const int row = q / (TC / 8), pc = (q % (TC / 8)) ^ (row & 31);
-            const int cr = row < rows_left ? row : rows_left - 1;
-            const int cc = 8 * pc < cols_left ? 8 * pc : cols_left - 8;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t *)(&s_w[0][0] + 512 * (wc + NW * i)), 16,
-                                                     (int)(2u * ((uint32_t)cr * (uint32_t)tile.ldw + (uint32_t)cc)), 0, 0, 2 /* non-temporal */);
-        }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-
-    // ---- row operands into LDS, visible to the workgroup without waiting for W
     auto stash_b = [&](const BPiece &v, int slot) {
         *reinterpret_cast<BPiece *>(&s_b[slot][tid / BPR][(BB / 2) * (tid % BPR)]) = v;
     };
-#pragma unroll
-    for (int s = 0; s < NS; ++s) stash_b(vb[s], s);
-    lds_barrier();
 
     float16_t acc[2][2];
 #pragma unroll
@@ -192,51 +167,92 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.0f;
-
-    // ---- the contraction, while the W tile lands
     float c_last = 0.0f;
+
+    // The k-steps run in phases of SP (one phase unless the tile takes more than 16): the registers
+    // hold one phase's operands.  The W tile is requested in the FIRST phase, behind that phase's
+    // operands; the later phases' operands land behind it and are contracted once it is there
+    // (requesting W in the last phase instead leaves the workgroup without W traffic for most of
+    // its life: 10.4 against 10.1 ms at rank 128 in place).
 #pragma unroll
-    for (int s = 0; s < STEPS; ++s) {
-        if (s % KS == 0 && in_use(s)) {  // a new expert: rescale what is accumulated so far (uniform branch, no loads inside)
-            const float c = terms.c[s / KS];
-            if (c_last != 0.0f) {
-                const float ratio = c_last / c;
+    for (int ph = 0; ph < PH; ++ph) {
+        const int s0 = SP * ph;
+        // ---- requests: operands first, the W tile last
+        BPiece vb[SP];
+        uint4_t xq[XD][2];
 #pragma unroll
-                for (int rb = 0; rb < 2; ++rb)
+        for (int s = 0; s < SP; ++s) fetch_b(vb[s], s0 + s);
 #pragma unroll
-                    for (int cb = 0; cb < 2; ++cb)
+        for (int s = 0; s < XD; ++s) fetch_x(xq[s], s0 + s);
+        __builtin_amdgcn_sched_barrier(0);
+        if (ph == 0) {
+            // W: wave w's instruction i fills the 1 KB of LDS that starts at piece slot 64 (w + NW i);
+            // lane l delivers slot 64 (w + NW i) + l, i.e. the piece of the row that w_slot puts there.
+            // Rows and columns beyond the matrix edge are clamped to valid ones and never stored.
+            const __amdgpu_buffer_rsrc_t rs = make_buffer(tile.w_src, 0xffffffffu);
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) acc[rb][cb][v] *= ratio;
+            for (int i = 0; i < WQ; ++i) {
+                const int q = 64 * (wc + NW * i) + lane;
+                const int row = q / (TC / 8), pc = (q % (TC / 8)) ^ (row & 31);
+                const int cr = row < rows_left ? row : rows_left - 1;
+                const int cc = 8 * pc < cols_left ? 8 * pc : cols_left - 8;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t *)(&s_w[0][0] + 512 * (wc + NW * i)), 16,
+                                                         (int)(2u * ((uint32_t)cr * (uint32_t)tile.ldw + (uint32_t)cc)), 0, 0, 2 /* non-temporal */);
             }
-            c_last = c;
         }
-        uint32_t d[8];
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- row operands into LDS, visible to the workgroup without waiting for W
+        if (ph > 0) lds_barrier();  // every wave is done reading the previous phase's pieces
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            uint32_t r[4] = {xq[s % XD][j][0], xq[s % XD][j][1], xq[s % XD][j][2], xq[s % XD][j][3]};
-            transpose_lanes_8_16(r);
+        for (int s = 0; s < NS; ++s) stash_b(vb[s], s);
+        lds_barrier();
+
+        // ---- the contraction (in the first phase: while the W tile lands)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) d[4 * j + i] = r[i];
-        }
-        const uint4_t xe = {__builtin_amdgcn_perm(d[1], d[0], 0x05040100u), __builtin_amdgcn_perm(d[3], d[2], 0x05040100u),
-                            __builtin_amdgcn_perm(d[5], d[4], 0x05040100u), __builtin_amdgcn_perm(d[7], d[6], 0x05040100u)};
-        const uint4_t xo = {__builtin_amdgcn_perm(d[1], d[0], 0x07060302u), __builtin_amdgcn_perm(d[3], d[2], 0x07060302u),
-                            __builtin_amdgcn_perm(d[5], d[4], 0x07060302u), __builtin_amdgcn_perm(d[7], d[6], 0x07060302u)};
-        const bf16x8_t x0 = __builtin_bit_cast(bf16x8_t, xe), x1 = __builtin_bit_cast(bf16x8_t, xo);
-        if (s + XD < STEPS) fetch_x(xq[s % XD], s + XD);  // the slot is consumed: refill it
+        for (int s = 0; s < SP; ++s) {
+            const int step = s0 + s;
+            if (step % KS == 0 && in_use(step)) {  // a new expert: rescale what is accumulated so far (uniform branch, no loads inside)
+                const float c = terms.c[step / KS];
+                if (c_last != 0.0f) {
+                    const float ratio = c_last / c;
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            const uint4_t y = *reinterpret_cast<const uint4_t *>(&s_b[s % NS][32 * rb + n][8 * h]);
-            const bf16x8_t yy = __builtin_bit_cast(bf16x8_t, y);
-            acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0, yy, acc[rb][0], 0, 0, 0);
-            acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1, yy, acc[rb][1], 0, 0, 0);
-        }
-        if (s + NS < STEPS) {  // the ring turns: k-step s + NS takes this slot
-            lds_barrier();     // every wave is done reading it
-            stash_b(vb[s + NS], s % NS);
-            // the refill is visible to its readers through the barrier of the next
-            // k-step, or, when no further slot turns, through this one
-            if (s + 1 + NS >= STEPS) lds_barrier();
+                    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) acc[rb][cb][v] *= ratio;
+                }
+                c_last = c;
+            }
+            uint32_t d[8];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                uint32_t r[4] = {xq[s % XD][j][0], xq[s % XD][j][1], xq[s % XD][j][2], xq[s % XD][j][3]};
+                transpose_lanes_8_16(r);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) d[4 * j + i] = r[i];
+            }
+            const uint4_t xe = {__builtin_amdgcn_perm(d[1], d[0], 0x05040100u), __builtin_amdgcn_perm(d[3], d[2], 0x05040100u),
+                                __builtin_amdgcn_perm(d[5], d[4], 0x05040100u), __builtin_amdgcn_perm(d[7], d[6], 0x05040100u)};
+            const uint4_t xo = {__builtin_amdgcn_perm(d[1], d[0], 0x07060302u), __builtin_amdgcn_perm(d[3], d[2], 0x07060302u),
+                                __builtin_amdgcn_perm(d[5], d[4], 0x07060302u), __builtin_amdgcn_perm(d[7], d[6], 0x07060302u)};
+            const bf16x8_t x0 = __builtin_bit_cast(bf16x8_t, xe), x1 = __builtin_bit_cast(bf16x8_t, xo);
+            if (s + XD < SP) fetch_x(xq[s % XD], step + XD);  // the slot is consumed: refill it
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                const uint4_t y = *reinterpret_cast<const uint4_t *>(&s_b[s % NS][32 * rb + n][8 * h]);
+                const bf16x8_t yy = __builtin_bit_cast(bf16x8_t, y);
+                acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0, yy, acc[rb][0], 0, 0, 0);
+                acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1, yy, acc[rb][1], 0, 0, 0);
+            }
+            if (s + NS < SP) {  // the ring turns: k-step s + NS of the phase takes this slot
+                lds_barrier();  // every wave is done reading it
+                stash_b(vb[s + NS], s % NS);
+                // the refill is visible to its readers through the barrier of the next
+                // k-step, or, when no further slot turns, through this one
+                if (s + 1 + NS >= SP) lds_barrier();
+            }
         }
     }
 
