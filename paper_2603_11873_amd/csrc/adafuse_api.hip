@@ -132,44 +132,39 @@ bool launch_mfma_any(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t
 
 // Which form of the rank-looped kernel runs (rank, term bucket): the unrolled kernel up to
 // 7 k-steps of 16 rank indices per tile, the overlapped one (W straight into LDS,
-// contraction meanwhile) from 8 on, the run-time expert loop for what neither takes
-// (8 terms at the zero-padded ranks 4 and 8).  Measurement knob
-// ADAFUSE_GEMM_FORM: 1 = never the overlapped form, 2 = the expert loop for every launch
-// with 4 or more terms, 3 = the overlapped form for short contractions too.
-enum GemmForm { kFormUnrolled, kFormOverlap, kFormLoop };
+// contraction meanwhile) from 8 on.  Measurement knob ADAFUSE_GEMM_FORM: 1 = the unrolled
+// form wherever it can take the launch, 3 = the overlapped form for short contractions too.
+enum GemmForm { kFormUnrolled, kFormOverlap };
+
+constexpr bool can_unroll(int r, int nt) { return nt <= 2 || (nt == 4 && r <= 16); }  // every row operand fits beside the W tile
+constexpr bool can_overlap(int r, int nt) { return nt * ((r + 15) / 16) <= 64; }
 
 GemmForm pick_gemm_form(int r, int nt)
 {
     static const int knob = [] { const char *e = std::getenv("ADAFUSE_GEMM_FORM"); return e ? std::atoi(e) : 0; }();
     const int steps = nt * ((r + 15) / 16);
-    const bool can_overlap = r % 16 == 0 && steps <= 64;
-    const bool can_unroll = nt <= 2 || (nt == 4 && r <= 16);  // every row operand fits beside the W tile
-    const bool force_loop = knob == 2 && nt >= 4;
-    if (can_overlap && (steps >= 8 || knob == 3) && knob != 1 && !force_loop) return kFormOverlap;
-    if (can_unroll && !force_loop) return kFormUnrolled;
-    return kFormLoop;
+    if (!can_unroll(r, nt)) return kFormOverlap;
+    if (!can_overlap(r, nt)) return kFormUnrolled;
+    if (knob == 1) return kFormUnrolled;
+    if (knob == 3) return kFormOverlap;
+    return steps >= 8 ? kFormOverlap : kFormUnrolled;
 }
 
 template <int R, int NT, int NW>
 bool launch_gemm_form(const SwitchParams &p, int64_t n_tiles, hipStream_t s)
 {
+    static_assert(can_unroll(R, NT) || can_overlap(R, NT), "some form takes every (rank, terms)");
     const dim3 grid((unsigned)n_tiles), block(64 * NW);
     switch (pick_gemm_form(R, NT)) {
     case kFormOverlap:
-        if constexpr (R % 16 == 0 && NT * ((R + 15) / 16) <= 64) {
+        if constexpr (can_overlap(R, NT)) {
             hipLaunchKernelGGL((switch_gemm_overlap_kernel<R, NT, NW>), grid, block, 0, s, p);
             return true;
         }
         break;
     case kFormUnrolled:
-        if constexpr (NT <= 2 || (NT == 4 && R <= 16)) {
+        if constexpr (can_unroll(R, NT)) {
             hipLaunchKernelGGL((switch_gemm_kernel<R, NT, NW>), grid, block, 0, s, p);
-            return true;
-        }
-        break;
-    case kFormLoop:
-        if constexpr (NT >= 4) {
-            hipLaunchKernelGGL((switch_gemm_loop_kernel<R, NW>), grid, block, 0, s, p);
             return true;
         }
         break;
@@ -588,11 +583,8 @@ const char *adafuse_switch_kernel_name(const adafuse_ctx *ctx, int32_t k, int32_
     switch (ctx->kernel) {
     case ADAFUSE_KERNEL_MFMA: return copy_only ? "switch_copy_kernel" : "switch_mfma_kernel";
     case ADAFUSE_KERNEL_GEMM:
-        switch (pick_gemm_form(ctx->r, terms_bucket(n_terms > 0 ? n_terms : 1))) {
-        case kFormOverlap: return "switch_gemm_overlap_kernel";
-        case kFormUnrolled: return "switch_gemm_kernel";
-        default: return "switch_gemm_loop_kernel";
-        }
+        return pick_gemm_form(ctx->r, terms_bucket(n_terms > 0 ? n_terms : 1)) == kFormOverlap ? "switch_gemm_overlap_kernel"
+                                                                                                : "switch_gemm_kernel";
     default: return "switch_valu_kernel";
     }
 }

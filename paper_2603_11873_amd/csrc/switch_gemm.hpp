@@ -35,12 +35,11 @@
 // The W tile sits in LDS unpadded (32 KB), its 16-byte pieces permuted by the
 // row number (w_slot), which leaves 8 KB of a four-workgroups-per-CU share of
 // LDS for the row operands.
-// Three forms, by the number of k-steps (16 rank indices of one expert) a tile
+// Two forms, by the number of k-steps (16 rank indices of one expert) a tile
 // takes: switch_gemm_kernel<R, NT> below, fully unrolled with every row operand
 // resident, up to 7; switch_gemm_overlap_kernel<R, NT> (its own header) from 8
 // on, where the contraction is long enough to be worth running while the W tile
-// is still on its way; switch_gemm_loop_kernel<R> for the rest (8 terms at the
-// zero-padded ranks 4 and 8): a run-time loop over the experts.
+// is still on its way.
 // Gates stay out of the bf16 operands.  Experts are chained in ONE accumulator:
 //   acc = P_0;  acc = acc * (c_0/c_1) + P_1;  ...;  W' = rn_bf16(W + c_last * acc)
 // which equals W + sum_j c_j P_j up to fp32 rounding of the ratios (terms with a
@@ -374,210 +373,6 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
     // layout (column p of a group is accumulator cb = p&1, v = 4b + p/2); tile back out.
     // no term, or only zero coefficients: the bits pass through untouched (-0.0 stays -0.0)
     if (c_last != 0.0f) w_tile_update<TC>(s_w, acc, c_last, 0, lcol0, n, h);
-    __syncthreads();
-    w_tile_store<TC, NTHR, WQ>(s_w, tile, opaque_copy(tid));
-}
-
-// The same kernel for many experts (4 or more terms): a run-time loop over the
-// experts with the term list in LDS, one barrier per expert, the next expert's
-// row operand and the next column-operand chunk in flight.  Unrolling the
-// expert loop (as above) costs registers here, and with them a workgroup per CU,
-// which matters more than prefetch depth: this kernel is bound by latency per
-// workgroup.
-template <int R, int NW>
-__global__ __launch_bounds__(64 * NW) void switch_gemm_loop_kernel(SwitchParams p)
-{
-    static_assert(R % 16 == 0 || R == 8 || R == 4, "rank must be a multiple of the MFMA depth, or 4 or 8 (zero padded)");
-    constexpr int KS = (R + 15) / 16;   // k-steps per expert
-    constexpr bool kPadded = R < 16;    // one k-step whose rank indices >= R are zero
-    constexpr int TR = kGemmTileRows;   // tile rows
-    constexpr int RP = R < 8 ? 8 : R;   // rank padded to one 16-byte piece
-    constexpr int BP = R <= 16 ? 16 : R + 8;  // LDS row pitch of the staged B slice (bf16): a 16-byte pad once a row is longer than a k-step
-    constexpr int BV = TR * RP / 8;     // 16-byte pieces of one expert's B slice for the tile
-    constexpr int BQ = (BV + 64 * NW - 1) / (64 * NW);  // ... per thread
-    constexpr int NTHR = 64 * NW;
-    constexpr int TC = kGemmWaveCols * NW;  // tile columns
-    constexpr int WQ = TR * TC / 8 / (64 * NW);  // 16-byte pieces of the W tile per thread
-
-    __shared__ int32_t s_e[kMaxTerms];
-    __shared__ float s_c[kMaxTerms];
-    __shared__ __align__(16) uint16_t s_b[2][TR][BP];  // row operand of the current / next expert
-    __shared__ __align__(16) uint16_t s_w[TR][TC];     // the W tile, on its way in and out (pieces permuted: w_slot)
-    {
-        Terms terms;
-        if (!load_terms<kMaxTerms>(p, terms)) return;
-        if (threadIdx.x == 0) {
-#pragma unroll
-            for (int j = 0; j < kMaxTerms; ++j) {
-                s_e[j] = terms.e[j];
-                s_c[j] = terms.c[j];
-            }
-        }
-    }
-
-    const TileDev tile = p.tiles[blockIdx.x];
-    const MatDev m = p.mats[tile.mat];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wr = 0, wc = wave;
-    const int n = lane & 31;   // row inside a 32-row block (MFMA N index)
-    const int h = lane >> 5;   // which half of the k-step / of a 16-column group
-
-    const int lrow0 = 64 * wr;                         // wave origin inside the tile
-    const int lcol0 = 64 * wc;
-    const int rows_left = tile.rows_left, cols_left = tile.cols_left;
-
-    // ---- W first.  The 32x32 result layout gives a lane 16-byte pieces of 32
-    // different rows, which streams badly; so the workgroup moves its W tile with
-    // row-contiguous accesses (a wave instruction = whole 512-byte row pieces) and
-    // turns it into the result layout through LDS, both ways.  Out-of-range pieces
-    // read a clamped (valid) address -- unconditional loads schedule freely -- and
-    // are never stored.
-    uint4_t wreg[WQ];
-    w_tile_request<TC, NTHR>(wreg, tile, tid);
-    __syncthreads();  // term list visible
-
-    float16_t acc[2][2];
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.0f;
-
-    // Column operand addressing, clamped the same way: a column beyond the edge
-    // only feeds result columns that are never stored.
-    int acol = lcol0 + 2 * n;                                  // this lane's column pair, inside the tile
-    acol = tile.col0 + (acol < cols_left ? acol : cols_left - 2);
-
-    // The row operand of one expert for the whole tile -- TR rows x R, contiguous in
-    // the B bank -- is fetched by the workgroup in 16-byte pieces (fully coalesced)
-    // and kept in LDS; rows beyond the edge repeat the last row.
-    // (operand loads through buffer descriptors, as in the kernel above)
-    const uint32_t b_bytes = (uint32_t)(m.out - tile.row0) * R * 2u;
-    auto fetch_b = [&](uint4_t (&v)[BQ], int e) {
-        const __amdgpu_buffer_rsrc_t rs = make_buffer(m.b_bank + ((size_t)e * m.out + tile.row0) * R, b_bytes);
-#pragma unroll
-        for (int i = 0; i < BQ; ++i) {
-            const int q = tid + NTHR * i;
-            const int row = q / (RP / 8), piece = q % (RP / 8);
-            const int cr = row < rows_left ? row : rows_left - 1;
-            if (q < BV) {
-                if constexpr (R >= 8) {
-                    v[i] = ld_buffer_b128(rs, 2u * ((uint32_t)cr * R + 8u * piece), 0u);
-                } else {  // rank 4: a row is 8 bytes
-                    const uint2_t t = ld_buffer_b64(rs, 2u * (uint32_t)cr * R, 0u);
-                    v[i] = uint4_t{t[0], t[1], 0u, 0u};
-                }
-            }
-        }
-    };
-    auto stash_b = [&](const uint4_t (&v)[BQ], int buf) {
-#pragma unroll
-        for (int i = 0; i < BQ; ++i) {
-            const int q = tid + NTHR * i;
-            const int row = q / (RP / 8), piece = q % (RP / 8);
-            if (q < BV) {
-                *reinterpret_cast<uint4_t *>(&s_b[buf][row][8 * piece]) = v[i];
-                if constexpr (kPadded)  // second half of the single k-step: zeros
-                    *reinterpret_cast<uint4_t *>(&s_b[buf][row][8]) = uint4_t{0u, 0u, 0u, 0u};
-            }
-        }
-    };
-    // Column operands are fetched a chunk (KCH k-steps = 16 KCH rank indices) ahead.
-    constexpr int KCH = KS >= 8 ? 2 : (KS >= 4 ? 4 : KS);
-    constexpr int NCH = KS / KCH;
-    struct XChunk {
-        uint32_t d[KCH][8];
-    };
-    const uint32_t in_bytes = 2u * (uint32_t)m.in;
-    const uint32_t xoff = 8u * h * in_bytes + 2u * (uint32_t)acol;  // rank index 8h of a k-step, this lane's columns
-    auto fetch_x = [&](XChunk &x, int e, int kc) {
-        const __amdgpu_buffer_rsrc_t rs = make_buffer(m.a_bank + (size_t)e * R * m.in, (uint32_t)R * in_bytes);
-#pragma unroll
-        for (int s2 = 0; s2 < KCH; ++s2)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                x.d[s2][i] = ld_buffer_b32(rs, xoff, (uint32_t)(16 * (KCH * kc + s2) + i) * in_bytes);  // zero beyond a padded rank (range check)
-            }
-    };
-    auto term_coeff = [&](int j) { return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(s_c[j]))); };
-    auto term_expert = [&](int j) { return __builtin_amdgcn_readfirstlane(s_e[j]); };
-    // every lane reads the same term list, so this is scalar control flow
-    auto next_term = [&](int j, int nt_) {
-        while (j < nt_ && term_coeff(j) == 0.0f) ++j;  // a zero coefficient contributes nothing: skipped
-        return j;
-    };
-
-    const int nt = p.inplace ? (p.mode == 2 ? 2 * p.k : p.k) : p.k;
-    float c_last = 0.0f;
-    int j = next_term(0, nt);
-    int buf = 0;
-    uint4_t vb[BQ];
-    XChunk xcur, xnxt;
-    if (j < nt) {
-        fetch_b(vb, term_expert(j));
-        fetch_x(xcur, term_expert(j), 0);
-    }
-    // W tile into LDS now (its loads were issued first, so they are the first to land):
-    // the registers are free for the contraction
-    w_tile_park<TC, NTHR>(s_w, wreg, tid);
-    if (j < nt) stash_b(vb, 0);
-    __syncthreads();
-    while (j < nt) {
-        const float c = term_coeff(j);
-        const int e = term_expert(j);
-        const int jn = next_term(j + 1, nt);
-        if (jn < nt) fetch_b(vb, term_expert(jn));  // next expert's row operand: in flight during this expert's MFMAs
-        if (c_last != 0.0f) {
-            const float ratio = c_last / c;
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[rb][cb][v] *= ratio;
-        }
-        c_last = c;
-#pragma unroll 1
-        for (int kc = 0; kc < NCH; ++kc) {
-            if (kc + 1 < NCH)
-                fetch_x(xnxt, e, kc + 1);
-            else if (jn < nt)
-                fetch_x(xnxt, term_expert(jn), 0);
-#pragma unroll
-            for (int s2 = 0; s2 < KCH; ++s2) {
-                const uint32_t *d = xcur.d[s2];
-                const int ks = kc * KCH + s2;
-                uint4_t y[2];
-#pragma unroll
-                for (int rb = 0; rb < 2; ++rb)
-                    y[rb] = *reinterpret_cast<const uint4_t *>(&s_b[buf][lrow0 + 32 * rb + n][16 * ks + 8 * h]);
-                const uint4_t xe = {__builtin_amdgcn_perm(d[1], d[0], 0x05040100u), __builtin_amdgcn_perm(d[3], d[2], 0x05040100u),
-                                    __builtin_amdgcn_perm(d[5], d[4], 0x05040100u), __builtin_amdgcn_perm(d[7], d[6], 0x05040100u)};
-                const uint4_t xo = {__builtin_amdgcn_perm(d[1], d[0], 0x07060302u), __builtin_amdgcn_perm(d[3], d[2], 0x07060302u),
-                                    __builtin_amdgcn_perm(d[5], d[4], 0x07060302u), __builtin_amdgcn_perm(d[7], d[6], 0x07060302u)};
-                const bf16x8_t x0 = __builtin_bit_cast(bf16x8_t, xe), x1 = __builtin_bit_cast(bf16x8_t, xo);
-#pragma unroll
-                for (int rb = 0; rb < 2; ++rb) {
-                    const bf16x8_t yy = __builtin_bit_cast(bf16x8_t, y[rb]);
-                    acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0, yy, acc[rb][0], 0, 0, 0);
-                    acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1, yy, acc[rb][1], 0, 0, 0);
-                }
-            }
-            xcur = xnxt;
-        }
-        if (jn < nt) stash_b(vb, buf ^ 1);
-        __syncthreads();  // next buffer complete, and everyone is done reading this one before it is reused
-        buf ^= 1;
-        j = jn;
-    }
-
-    // ---- epilogue: each lane updates its pieces of the W tile in LDS, in the result
-    // layout (column p of a group is accumulator cb = p&1, v = 4b + p/2); tile back out.
-    // no term, or only zero coefficients: the bits pass through untouched (-0.0 stays -0.0)
-    if (c_last != 0.0f) w_tile_update<TC>(s_w, acc, c_last, lrow0, lcol0, n, h);
     __syncthreads();
     w_tile_store<TC, NTHR, WQ>(s_w, tile, opaque_copy(tid));
 }

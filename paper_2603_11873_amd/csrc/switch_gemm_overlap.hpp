@@ -86,8 +86,9 @@ __device__ __forceinline__ void w_tile_update_grouped(uint16_t (*s_w)[TC], const
 template <int R, int NT, int NW>
 __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchParams p)
 {
-    static_assert(R % 16 == 0, "whole k-steps");
-    constexpr int KS = R / 16;      // k-steps per expert
+    static_assert(R % 16 == 0 || R == 8 || R == 4, "rank: a multiple of 16, or 4 or 8 (zero padded to one k-step)");
+    constexpr int KS = (R + 15) / 16;  // k-steps per expert
+    constexpr int RK = R < 16 ? R : 16;  // rank indices of a k-step that exist
     constexpr int STEPS = NT * KS;  // k-steps per tile
     constexpr int SP = STEPS <= 16 ? STEPS : 16;  // k-steps per phase
     constexpr int PH = STEPS / SP;                // phases
@@ -138,7 +139,8 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
     const uint32_t xoff = (uint32_t)(8 * h + (n >> 3)) * in_bytes + 2u * (uint32_t)acol;
     constexpr int BPR = 32 / BB;  // threads per row of the piece
     const int brow = tid / BPR < rows_left ? tid / BPR : rows_left - 1;
-    const uint32_t boff = 2u * (uint32_t)brow * R + (uint32_t)BB * (tid % BPR);
+    // the thread's BB bytes of a 32-byte piece row; beyond a padded rank: an offset outside the descriptor, which reads as zero
+    const uint32_t boff = BB * (tid % BPR) < 2 * RK ? 2u * (uint32_t)brow * R + (uint32_t)BB * (tid % BPR) : 0xffffff00u;
     const uint32_t b_bytes = (uint32_t)(m.out - tile.row0) * R * 2u;
     auto in_use = [&](int step) { return step / KS < nt && terms.c[step / KS] != 0.0f; };
     auto fetch_b = [&](BPiece &v, int step) {
@@ -151,7 +153,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
     };
     auto fetch_x = [&](uint4_t (&d)[2], int step) {
         const __amdgpu_buffer_rsrc_t rs = make_buffer(m.a_bank + ((size_t)terms.e[step / KS] * R + 16 * (step % KS)) * m.in,
-                                                      in_use(step) ? 16u * in_bytes : 0u);
+                                                      in_use(step) ? (uint32_t)RK * in_bytes : 0u);  // rank indices beyond a padded rank read as zero
         d[0] = ld_buffer_b128(rs, xoff, 0u);
         d[1] = ld_buffer_b128(rs, xoff, 4u * in_bytes);
     };

@@ -604,13 +604,13 @@ def test_per_matrix_launches_give_the_same_bits(oracle):
 @pytest.mark.parametrize("r,k,inplace", [(64, 2, False), (128, 2, False), (64, 2, True), (16, 4, False), (32, 1, True),
                                          (32, 4, False), (64, 4, False), (32, 2, True), (32, 3, False), (16, 3, False),
                                          (16, 4, True), (8, 4, True), (128, 4, False), (64, 3, True), (16, 3, True),
-                                         (128, 1, False), (32, 4, True), (32, 2, False), (128, 4, True), (128, 3, True)])
+                                         (128, 1, False), (32, 4, True), (32, 2, False), (128, 4, True), (128, 3, True), (4, 4, True), (8, 3, True)])
 def test_rank_looped_kernel_modes(oracle, r, k, inplace):
-    """The rank-looped kernels in all their forms -- unrolled (up to 7 k-steps of 16 rank indices per
-    tile), overlapped with the W fetch (8 to 64 k-steps in phases of 16: e.g. top-2 at ranks 64 and
-    128, 4 terms at ranks 32 to 128, 8 terms at ranks 16 to 128, also with terms left unused: k = 3)
-    and the run-time expert loop (8 terms at the zero-padded ranks 4 and 8): MERGE / SWAP / UNMERGE,
-    out of place and in place, two ragged matrices."""
+    """The rank-looped kernels in both forms -- unrolled (up to 7 k-steps of 16 rank indices per
+    tile) and overlapped with the W fetch (8 to 64 k-steps in phases of 16: e.g. top-2 at ranks 64
+    and 128, 4 terms at ranks 32 to 128, 8 terms at any rank, the zero-padded rank 8 included; also
+    with terms left unused: k = 3): MERGE / SWAP / UNMERGE, out of place and in place, two ragged
+    matrices."""
     dev = torch.device("cuda:0")
     g = torch.Generator().manual_seed(r * 10 + k)
     E = 4
@@ -668,7 +668,8 @@ def test_rank_looped_kernel_modes(oracle, r, k, inplace):
     (64, 2, False, "SWAP", "switch_gemm_overlap_kernel"), (128, 2, False, "MERGE", "switch_gemm_overlap_kernel"),
     (32, 2, True, "SWAP", "switch_gemm_overlap_kernel"), (32, 2, True, "MERGE", "switch_gemm_kernel"),
     (128, 4, False, "SWAP", "switch_gemm_overlap_kernel"), (128, 4, True, "SWAP", "switch_gemm_overlap_kernel"),
-    (8, 4, True, "SWAP", "switch_gemm_loop_kernel"), (64, 2, False, "UNMERGE", "switch_gemm_kernel"),
+    (8, 4, True, "SWAP", "switch_gemm_overlap_kernel"), (8, 2, True, "SWAP", "switch_gemm_kernel"),
+    (64, 2, False, "UNMERGE", "switch_gemm_kernel"),
 ])
 def test_switch_kernel_name_follows_the_dispatch(r, k, inplace, mode, expect):
     """The label measurements use for a launch is the form the library would run: by the
