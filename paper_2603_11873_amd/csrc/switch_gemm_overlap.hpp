@@ -125,9 +125,10 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
     const int lcol0 = 64 * wc;
     const int rows_left = tile.rows_left, cols_left = tile.cols_left;
 
-    // operand addressing as in the ring kernel: one descriptor per k-step, one offset
-    // register per lane; a k-step of an expert that is not in use gets an empty
-    // descriptor (zeros without a memory access), so all of this is straight-line code
+    // Operand addressing: one descriptor per k-step, one offset register per lane; a
+    // k-step of an expert that is not in use gets an empty descriptor (zeros without a
+    // memory access), so all of this is straight-line code and the compiler's wait
+    // counts are exact.
     // Column operand: 16-byte loads (8 columns of one rank index; twice the bytes per L1
     // cycle of 4-byte loads, and the L1 is what this kernel keeps busiest).  Lane n = t + 8 a
     // (t < 8, a < 4) loads the wave's columns 8 t .. 8 t + 7 at rank indices 8 h + a and
