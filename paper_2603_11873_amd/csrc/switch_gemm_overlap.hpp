@@ -259,7 +259,9 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
         }
     }
 
-    // ---- the W tile has to be there now: the fence of this barrier waits for every wave's transfers
+    // ---- the W tile has to be there now: every wave waits for its own transfers (the fence of
+    // the barrier makes the compiler wait as well; the explicit wait does not depend on that)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (c_last != 0.0f) w_tile_update_grouped<TC>(s_w, acc, c_last, lcol0, n, h);
     __syncthreads();
