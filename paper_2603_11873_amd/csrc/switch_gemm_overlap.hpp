@@ -103,10 +103,16 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
     constexpr int NTHR = 64 * NW;
     constexpr int TR = kGemmTileRows, TC = kGemmWaveCols * NW;
     constexpr int WQ = TR * TC / 8 / NTHR;
-    static_assert(SP + 2 * XD + WQ <= 63, "outstanding loads");
-    constexpr int BB = TR * 32 / NTHR;  // bytes of one k-step of the row operand (64 rows x 32 B) per thread
-    static_assert(BB == 8 || BB == 4, "4 or 8 waves");
-    using BPiece = typename std::conditional<BB == 8, uint2_t, uint32_t>::type;
+    // Row-operand pieces (one k-step: 64 rows x 32 B) are fetched G at a time: two neighbouring
+    // k-steps of an expert with one load where an expert has more than one (16 bytes per lane
+    // with 4 waves: the L1 delivers twice the bytes per cycle to such loads), else one.
+    constexpr int G = KS >= 2 ? 2 : 1;
+    constexpr int TPK = NTHR / G;    // threads that share one piece
+    constexpr int BT = 2048 / TPK;   // bytes of it per thread
+    static_assert(BT == 16 || BT == 8 || BT == 4, "4 or 8 waves");
+    using BPiece = typename std::conditional<BT == 16, uint4_t, typename std::conditional<BT == 8, uint2_t, uint32_t>::type>::type;
+    static_assert(SP % G == 0, "whole groups");
+    static_assert(SP / G + 2 * XD + WQ <= 63, "outstanding loads");
 
     __shared__ __align__(16) uint16_t s_b[NS][TR][16];
     __shared__ __align__(16) uint16_t s_w[TR][TC];  // pieces permuted: w_slot
@@ -138,16 +144,20 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
     acol = tile.col0 + (acol < cols_left ? acol : cols_left - 8);
     const uint32_t in_bytes = 2u * (uint32_t)m.in;
     const uint32_t xoff = (uint32_t)(8 * h + (n >> 3)) * in_bytes + 2u * (uint32_t)acol;
-    constexpr int BPR = 32 / BB;  // threads per row of the piece
-    const int brow = tid / BPR < rows_left ? tid / BPR : rows_left - 1;
-    // the thread's BB bytes of a 32-byte piece row; beyond a padded rank: an offset outside the descriptor, which reads as zero
-    const uint32_t boff = BB * (tid % BPR) < 2 * RK ? 2u * (uint32_t)brow * R + (uint32_t)BB * (tid % BPR) : 0xffffff00u;
+    constexpr int BPR = 32 / BT;     // threads per row of a piece
+    const int bwhich = tid / TPK;    // which piece of the group this thread works on
+    const int brow_t = (tid % TPK) / BPR, bpart = (tid % TPK) % BPR;
+    const int brow = brow_t < rows_left ? brow_t : rows_left - 1;
+    // the thread's BT bytes of a 32-byte piece row; beyond a padded rank: an offset outside the descriptor, which reads as zero
+    const uint32_t boff = BT * bpart < 2 * RK ? 2u * (uint32_t)brow * R + 32u * bwhich + (uint32_t)BT * bpart : 0xffffff00u;
     const uint32_t b_bytes = (uint32_t)(m.out - tile.row0) * R * 2u;
     auto in_use = [&](int step) { return step / KS < nt && terms.c[step / KS] != 0.0f; };
-    auto fetch_b = [&](BPiece &v, int step) {
+    auto fetch_b = [&](BPiece &v, int step) {  // the group of pieces that starts at k-step `step`
         const __amdgpu_buffer_rsrc_t rs =
             make_buffer(m.b_bank + ((size_t)terms.e[step / KS] * m.out + tile.row0) * R, in_use(step) ? b_bytes : 0u);
-        if constexpr (BB == 8)
+        if constexpr (BT == 16)
+            v = ld_buffer_b128(rs, boff, 32u * (step % KS));
+        else if constexpr (BT == 8)
             v = ld_buffer_b64(rs, boff, 32u * (step % KS));
         else
             v = ld_buffer_b32(rs, boff, 32u * (step % KS));
@@ -159,8 +169,8 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
         d[1] = ld_buffer_b128(rs, xoff, 4u * in_bytes);
     };
 
-    auto stash_b = [&](const BPiece &v, int slot) {
-        *reinterpret_cast<BPiece *>(&s_b[slot][tid / BPR][(BB / 2) * (tid % BPR)]) = v;
+    auto stash_b = [&](const BPiece &v, int slot) {  // the group goes into slots slot .. slot + G - 1
+        *reinterpret_cast<BPiece *>(&s_b[slot + bwhich][brow_t][(BT / 2) * bpart]) = v;
     };
 
     float16_t acc[2][2];
@@ -181,10 +191,10 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
     for (int ph = 0; ph < PH; ++ph) {
         const int s0 = SP * ph;
         // ---- requests: operands first, the W tile last
-        BPiece vb[SP];
+        BPiece vb[SP / G];
         uint4_t xq[XD][2];
 #pragma unroll
-        for (int s = 0; s < SP; ++s) fetch_b(vb[s], s0 + s);
+        for (int g = 0; g < SP / G; ++g) fetch_b(vb[g], s0 + G * g);
 #pragma unroll
         for (int s = 0; s < XD; ++s) fetch_x(xq[s], s0 + s);
         __builtin_amdgcn_sched_barrier(0);
@@ -208,7 +218,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
         // ---- row operands into LDS, visible to the workgroup without waiting for W
         if (ph > 0) lds_barrier();  // every wave is done reading the previous phase's pieces
 #pragma unroll
-        for (int s = 0; s < NS; ++s) stash_b(vb[s], s);
+        for (int g = 0; g < NS / G; ++g) stash_b(vb[g], G * g);
         lds_barrier();
 
         // ---- the contraction (in the first phase: while the W tile lands)
@@ -249,11 +259,11 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
                 acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x0, yy, acc[rb][0], 0, 0, 0);
                 acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x1, yy, acc[rb][1], 0, 0, 0);
             }
-            if (s + NS < SP) {  // the ring turns: k-step s + NS of the phase takes this slot
-                lds_barrier();  // every wave is done reading it
-                stash_b(vb[s + NS], s % NS);
+            if ((s + 1) % G == 0 && s + 1 - G + NS < SP) {  // the ring turns: the group G (s / G) + NS takes the slots of group s / G
+                lds_barrier();  // every wave is done reading them
+                stash_b(vb[s / G + NS / G], (s + 1 - G) % NS);
                 // the refill is visible to its readers through the barrier of the next
-                // k-step, or, when no further slot turns, through this one
+                // turn, or, when no further slot turns, through this one
                 if (s + 1 + NS >= SP) lds_barrier();
             }
         }
