@@ -50,9 +50,9 @@ def parse_args():
     return ap.parse_args()
 
 
-def read_traffic(workload, kernel_name):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", f"switch_{kernel_name}_{workload}_pmc.txt")
+def read_traffic(workload, kernel_fn):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this kernel and workload, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"{kernel_fn.replace('_kernel', '')}_{workload}_pmc.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -228,7 +228,7 @@ def main():
                    "step": "pregate(1 token) + fused_switch(all matrices), one stream"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": read_traffic(wl.name, kernel_name) if mode == af.SWAP and not args.inplace else None,
+                     "traffic": read_traffic(wl.name, ctx.switch_kernel_name(wl.k, mode)) if mode == af.SWAP and not args.inplace else None,
                      "kernel": ctx.switch_kernel_name(wl.k, mode),
                      "algorithmic_bytes_per_launch": alg_bytes, "early_out_launches_excluded": early_outs,
                      "matrix_core": {"achieved": alg_flops / avg_kernel_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
