@@ -155,7 +155,8 @@ bool launch_gemm_form(const SwitchParams &p, int64_t n_tiles, hipStream_t s)
 {
     static_assert(can_unroll(R, NT) || can_overlap(R, NT), "some form takes every (rank, terms)");
     const dim3 grid((unsigned)n_tiles), block(64 * NW);
-    switch (pick_gemm_form(R, NT)) {
+    // a plain copy (no term: out-of-place UNMERGE) has nothing to overlap; W first, through registers, is the faster copy
+    switch (p.k == 0 && can_unroll(R, NT) ? kFormUnrolled : pick_gemm_form(R, NT)) {
     case kFormOverlap:
         if constexpr (can_overlap(R, NT)) {
             hipLaunchKernelGGL((switch_gemm_overlap_kernel<R, NT, NW>), grid, block, 0, s, p);
@@ -600,8 +601,8 @@ const char *adafuse_switch_kernel_name(const adafuse_ctx *ctx, int32_t k, int32_
     switch (ctx->kernel) {
     case ADAFUSE_KERNEL_MFMA: return copy_only ? "switch_copy_kernel" : "switch_mfma_kernel";
     case ADAFUSE_KERNEL_GEMM:
-        return pick_gemm_form(ctx->r, terms_bucket(n_terms > 0 ? n_terms : 1)) == kFormOverlap ? "switch_gemm_overlap_kernel"
-                                                                                                : "switch_gemm_kernel";
+        if (copy_only) return "switch_gemm_kernel";
+        return pick_gemm_form(ctx->r, terms_bucket(n_terms)) == kFormOverlap ? "switch_gemm_overlap_kernel" : "switch_gemm_kernel";
     default: return "switch_valu_kernel";
     }
 }

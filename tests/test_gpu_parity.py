@@ -669,7 +669,7 @@ def test_rank_looped_kernel_modes(oracle, r, k, inplace):
     (32, 2, True, "SWAP", "switch_gemm_overlap_kernel"), (32, 2, True, "MERGE", "switch_gemm_kernel"),
     (128, 4, False, "SWAP", "switch_gemm_overlap_kernel"), (128, 4, True, "SWAP", "switch_gemm_overlap_kernel"),
     (8, 4, True, "SWAP", "switch_gemm_overlap_kernel"), (8, 2, True, "SWAP", "switch_gemm_kernel"),
-    (64, 2, False, "UNMERGE", "switch_gemm_kernel"),
+    (64, 2, False, "UNMERGE", "switch_gemm_kernel"), (128, 2, False, "UNMERGE", "switch_gemm_kernel"),
 ])
 def test_switch_kernel_name_follows_the_dispatch(r, k, inplace, mode, expect):
     """The label measurements use for a launch is the form the library would run: by the
