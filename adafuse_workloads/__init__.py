@@ -2,7 +2,10 @@
 
 This module serves both the HIP path and the CPU oracle and therefore holds
 none of the method's arithmetic: it only names the five workload shapes and
-draws random tensors (fp32 normal draws, rounded once to bf16).  The paper's
+draws random tensors (fp32 normal draws, rounded once to bf16).  The one thing it
+looks at is whether a drawn hidden state makes a clear-cut routing decision (a
+library fp64 matmul and a sort: gen_hidden redraws near-tie tokens), which is a
+property of the inputs, not a step of the path.  The paper's
 own workload (Llama2-7B fine-tuned experts, ShareGPT prompts; section
 "Experiment Setup") is not available offline and is not needed: the cost and
 the correctness of the switch depend on shapes and value ranges only.
@@ -129,17 +132,66 @@ def gen_router(wl: Workload, device="cpu") -> torch.Tensor:
     return _normal_bf16((wl.E, wl.d), 0.02, _gen(wl.seed, KIND_ROUTER, 0, 0, device), device)
 
 
+TIE_MARGIN = 1e-3   # smallest gap between neighbouring logits near the selection boundary, x the token's largest |logit|
+
+
+def _logits64(h: torch.Tensor, router: torch.Tensor) -> torch.Tensor:
+    """Library fp64 matmul of bf16-rounded hidden states with the router rows: [T][E]."""
+    return h.to(torch.bfloat16).double() @ router.double().T
+
+
+def _decisive(logits: torch.Tensor, k: int) -> torch.Tensor:
+    """Per token: are the k + 1 largest logits pairwise at least TIE_MARGIN x max|logit| apart?
+    Then no arithmetic that is accurate to 1e-5 can order them differently, and "the k largest,
+    in descending order" is one well-defined answer."""
+    top = torch.sort(logits, dim=1, descending=True).values[:, : k + 1]
+    if top.shape[1] < 2:
+        return torch.ones(logits.shape[0], dtype=torch.bool, device=logits.device)
+    gaps = (top[:, :-1] - top[:, 1:]).min(dim=1).values
+    return gaps >= TIE_MARGIN * logits.abs().max(dim=1).values
+
+
+def _top_set(logits_row: torch.Tensor, k: int):
+    return sorted(torch.topk(logits_row, k).indices.tolist())
+
+
 def gen_hidden(wl: Workload, device="cpu") -> torch.Tensor:
-    """[T][d] N(0,1).  With repeat_prob > 0, token t is h_{t-1} + 0.05*N(0,1) with that
-    probability, which usually keeps the router's expert set (not verified here)."""
+    """[T][d] N(0,1), rounded to bf16.
+
+    Near-tie tokens are redrawn: a token whose k + 1 largest router logits (library fp64
+    matmul against gen_router's rows) are not TIE_MARGIN apart is replaced by a fresh draw,
+    so the routing decision of every token is unambiguous at any reasonable precision.
+    With repeat_prob > 0, token t is h_{t-1} + 0.05*N(0,1) with that probability, redrawn
+    (up to 64 times) until it keeps the expert set of token t-1; the others are fresh draws.
+    """
     g = _gen(wl.seed, KIND_HIDDEN, 0, 0, device)
     h = torch.randn((wl.T, wl.d), generator=g, device=device, dtype=torch.float32)
-    if wl.repeat_prob > 0:
-        gr = _gen(wl.seed, KIND_REPEAT, 0, 0, "cpu")
-        rep = (torch.rand((wl.T,), generator=gr) < wl.repeat_prob).tolist()
-        for t in range(1, wl.T):
-            if rep[t]:
-                h[t] = h[t - 1] + 0.05 * h[t]
+    router = gen_router(wl, device)
+    draw = lambda n: torch.randn((n, wl.d), generator=g, device=device, dtype=torch.float32)
+    if wl.repeat_prob <= 0:
+        for _ in range(1000):
+            bad = ~_decisive(_logits64(h, router), wl.k)
+            n_bad = int(bad.sum())
+            if n_bad == 0:
+                break
+            h[bad] = draw(n_bad)
+        return h.to(torch.bfloat16)
+    gr = _gen(wl.seed, KIND_REPEAT, 0, 0, "cpu")
+    rep = (torch.rand((wl.T,), generator=gr) < wl.repeat_prob).tolist()
+    prev_set = None
+    for t in range(wl.T):
+        noise = h[t].clone()
+        for attempt in range(1000):
+            cand = h[t - 1] + 0.05 * noise if (t > 0 and rep[t]) else noise
+            lg = _logits64(cand[None, :], router)
+            ok = bool(_decisive(lg, wl.k)[0])
+            if ok and t > 0 and rep[t] and attempt < 64:
+                ok = _top_set(lg[0], wl.k) == prev_set   # after 64 tries a decisive token with a new set is accepted
+            if ok:
+                break
+            noise = draw(1)[0]
+        h[t] = cand
+        prev_set = _top_set(lg[0], wl.k)
     return h.to(torch.bfloat16)
 
 

@@ -151,7 +151,8 @@ const char *adafuse_switch_kernel_name(const adafuse_ctx *ctx, int32_t k, int32_
  *                   descending, expert index ascending); ties take the lower index
  *   gates[t][j]   = softmax per gate_norm, fp32
  * hidden   DEVICE bf16 [T][d], w_router DEVICE bf16 [E][d], both 16-byte aligned,
- *          d a multiple of 8; 1 <= k <= E <= 64; T >= 0 (T == 0 is a no-op).
+ *          d a multiple of 8; 1 <= E <= 64, 1 <= k <= min(E, 8) (else ERR_ARG);
+ *          T >= 0 (T == 0 is a no-op).
  * idx      DEVICE int32 [T][k], gates DEVICE fp32 [T][k], logits DEVICE fp32
  *          [T][E] or NULL.  Outputs are written by the kernel on `hip_stream`
  *          (a hipStream_t, NULL = default stream); the call does not wait.
@@ -174,7 +175,10 @@ adafuse_status adafuse_pregate(const void *hidden, const void *w_router,
  *         removed exactly (no bf16 drift) and Eq.8's signed concatenation needs
  *         no arithmetic.  prev, if not NULL, is only compared with next on the
  *         device: when both are bit-identical W_work already holds the result
- *         and the kernel returns without touching it.
+ *         and the kernel returns without touching it.  `scale` is not part of
+ *         that comparison: the caller's contract is that prev is what the last
+ *         call merged, with the same scale (after a change of scale, pass
+ *         prev = NULL or use MERGE).
  * In place (w_work == w_base; Eq.7-8 as printed), with dW(x) = s * sum_j g_j B_{e_j} A_{e_j}:
  *   MERGE   W <- rn_bf16(W + dW(next));  UNMERGE  W <- rn_bf16(W - dW(prev));
  *   SWAP    W <- rn_bf16(W - dW(prev) + dW(next)), the signed concatenation
@@ -187,7 +191,9 @@ adafuse_status adafuse_pregate(const void *hidden, const void *w_router,
  * synchronisation), so they may be recorded into a HIP graph.
  * Each W element is read once and written once (2 + 2 bytes); the selected A/B
  * slices are staged in registers and LDS.  Expert indices outside [0,E) in device memory are
- * clamped into range, not detected.  The call enqueues on `hip_stream` and
+ * clamped into range, not detected.  Gates may be any finite fp32 values (negative,
+ * tiny or sub-normal ones included): the experts are accumulated in ascending order
+ * of |s g_j|, so no intermediate ratio of coefficients can overflow.  The call enqueues on `hip_stream` and
  * returns; no host synchronisation.
  * Errors: NULL ctx or a NULL pointer the mode needs -> ERR_NULL; bad k or mode, or a
  * current device other than the one the context was created on -> ERR_ARG; launch

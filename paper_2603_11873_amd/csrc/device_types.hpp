@@ -171,4 +171,31 @@ __device__ __forceinline__ bool load_terms(const SwitchParams &p, Terms &t)
     return true;
 }
 
+// Order the term list by ascending |coefficient| (a fixed odd-even transposition
+// network: every index is a compile-time constant, the values are uniform and the
+// comparison is on the integer image of |c|, so the whole thing stays in scalar
+// registers).  Kernels that chain the experts in one accumulator,
+//   acc = P_0;  acc = acc * (c_0 / c_1) + P_1;  ...;  W' = W + c_last * acc,
+// then only ever form ratios of magnitude <= 1: a gate that is tiny or sub-normal
+// next to the others can no longer drive a ratio to infinity.  Terms with a zero
+// coefficient (unused slots included) come first and are skipped by their value.
+template <int NT>
+__device__ __forceinline__ void sort_terms_by_magnitude(Terms &t)
+{
+#pragma unroll
+    for (int round = 0; round < NT; ++round) {
+#pragma unroll
+        for (int a = round & 1; a + 1 < NT; a += 2) {
+            const uint32_t ma = __float_as_uint(t.c[a]) & 0x7fffffffu, mb = __float_as_uint(t.c[a + 1]) & 0x7fffffffu;
+            const bool swap = ma > mb;
+            const int32_t ea = t.e[a], eb = t.e[a + 1];
+            const float ca = t.c[a], cb = t.c[a + 1];
+            t.e[a] = swap ? eb : ea;
+            t.e[a + 1] = swap ? ea : eb;
+            t.c[a] = swap ? cb : ca;
+            t.c[a + 1] = swap ? ca : cb;
+        }
+    }
+}
+
 }  // namespace adafuse

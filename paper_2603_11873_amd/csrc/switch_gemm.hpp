@@ -40,10 +40,12 @@
 // resident, up to 7; switch_gemm_overlap_kernel<R, NT> (its own header) from 8
 // on, where the contraction is long enough to be worth running while the W tile
 // is still on its way.
-// Gates stay out of the bf16 operands.  Experts are chained in ONE accumulator:
-//   acc = P_0;  acc = acc * (c_0/c_1) + P_1;  ...;  W' = rn_bf16(W + c_last * acc)
-// which equals W + sum_j c_j P_j up to fp32 rounding of the ratios (terms with a
-// zero coefficient are skipped, so no ratio divides by zero).
+// Gates stay out of the bf16 operands.  Experts are chained in ONE accumulator,
+// in ascending order of |c_j| (sort_terms_by_magnitude):
+//   acc = P_0;  acc = acc * (c_0/c_1) + P_1;  ...;  W' = rn_bf16(fma(c_last, acc, W))
+// which equals W + sum_j c_j P_j up to fp32 rounding of the ratios.  Every ratio has
+// magnitude <= 1, so a tiny or sub-normal gate beside an ordinary one cannot overflow
+// it; terms with a zero coefficient are skipped, so no ratio divides by zero.
 #pragma once
 #include "device_types.hpp"
 
@@ -104,13 +106,11 @@ __device__ __forceinline__ void w_tile_update(uint16_t (*s_w)[TC], const float16
         for (int b = 0; b < 4; ++b) {
             uint4_t *slot = w_slot<TC>(s_w, lrow0 + 32 * rb + n, lcol0 / 8 + 2 * b + h);
             const uint4_t wv = *slot;
-            float o[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) o[q] = c * acc[rb][q & 1][4 * b + (q >> 1)];
             uint4_t out;
 #pragma unroll
-            for (int hh = 0; hh < 4; ++hh)
-                out[hh] = pack_bf16_rne(o[2 * hh] + bf16_lo(wv[hh]), o[2 * hh + 1] + bf16_hi(wv[hh]));
+            for (int hh = 0; hh < 4; ++hh)  // columns 2 hh, 2 hh + 1 of the piece: one fused multiply-add each, one rounding to bf16
+                out[hh] = pack_bf16_rne(__builtin_fmaf(c, acc[rb][0][4 * b + hh], bf16_lo(wv[hh])),
+                                        __builtin_fmaf(c, acc[rb][1][4 * b + hh], bf16_hi(wv[hh])));
             *slot = out;
         }
 }
@@ -191,7 +191,8 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
 
     Terms terms;
     if (!load_terms<NT>(p, terms)) return;
-    const int nt = p.inplace ? (p.mode == 2 ? 2 * p.k : p.k) : p.k;  // terms in use (the rest have coefficient 0)
+    sort_terms_by_magnitude<NT>(terms);  // ascending |c|: zero coefficients (unused slots too) first, skipped by value
+    auto in_use = [&](int j) { return terms.c[j] != 0.0f; };
 
     const TileDev tile = p.tiles[blockIdx.x];
     const MatDev m = p.mats[tile.mat];
@@ -272,19 +273,25 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
         for (int s2 = 0; s2 < KCH; ++s2)
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                // rank index 16 (KCH kc + s2) + 8h + i; beyond a padded rank the read is outside the
-                // expert's slice, for which the descriptor's range check returns zero
-                x.d[s2][i] = ld_buffer_b32(rs, xoff, (uint32_t)(16 * (KCH * kc + s2) + i) * in_bytes);
+                // rank index 16 (KCH kc + s2) + 8h + i.  Zero padding of ranks 4 and 8: an index the
+                // PER-LANE offset puts beyond the slice (h = 1: 8 rows in) fails the descriptor's range
+                // check and reads as zero; the uniform offset is not part of that check, so indices
+                // i >= R of the lower half are not loaded at all (rank 4: they would be the next
+                // expert's rows, or whatever follows the bank)
+                if (R < 8 && i >= R)
+                    x.d[s2][i] = 0u;
+                else
+                    x.d[s2][i] = ld_buffer_b32(rs, xoff, (uint32_t)(16 * (KCH * kc + s2) + i) * in_bytes);
             }
     };
 
     BReg vb[NB][BN];
 #pragma unroll
-    for (int j = 0; j < NB; ++j) fetch_b(vb[j], terms.e[j], j < nt);  // an unused term: empty descriptor, zeros
+    for (int j = 0; j < NB; ++j) fetch_b(vb[j], terms.e[j], in_use(j));  // an unused term: empty descriptor, zeros
     XChunk xq[QX];
 #pragma unroll
     for (int i = 0; i < QX; ++i)
-        if (i / NCH < nt) fetch_x(xq[i], terms.e[i / NCH], i % NCH);
+        if (in_use(i / NCH)) fetch_x(xq[i], terms.e[i / NCH], i % NCH);
     if constexpr (kOperandsFirst) {
         w_tile_request<TC, NTHR>(wreg, tile, tid);
 #pragma unroll
@@ -312,13 +319,13 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
         const float c = terms.c[j];
-        const bool active = j < nt && c != 0.0f;  // uniform; a zero coefficient contributes nothing
+        const bool active = c != 0.0f;  // uniform; a zero coefficient contributes nothing
         BReg vroll[BN];
         if constexpr (NT > NB) {
-            if (j + NB < NT) fetch_b(vroll, terms.e[j + NB], j + NB < nt);  // rolls into this expert's slot below
+            if (j + NB < NT) fetch_b(vroll, terms.e[j + NB], in_use(j + NB));  // rolls into this expert's slot below
         }
         if (active && c_last != 0.0f) {
-            const float ratio = c_last / c;
+            const float ratio = c_last / c;  // |ratio| <= 1: the terms come in ascending magnitude
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -343,7 +350,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_kernel(SwitchParams p)
                 x1[s2] = __builtin_bit_cast(bf16x8_t, xo);
             }
             // the slot is consumed: refill it with the chunk QX ahead
-            if (i + QX < TOT && (i + QX) / NCH < nt) fetch_x(x, terms.e[(i + QX) / NCH], (i + QX) % NCH);
+            if (i + QX < TOT && in_use((i + QX) / NCH)) fetch_x(x, terms.e[(i + QX) / NCH], (i + QX) % NCH);
             if (active) {
 #pragma unroll
                 for (int s2 = 0; s2 < KCH; ++s2) {

@@ -72,13 +72,11 @@ __device__ __forceinline__ void w_tile_update_grouped(uint16_t (*s_w)[TC], const
         for (int i = 0; i < 4; ++i) {
             uint4_t *slot = w_slot<TC>(s_w, 32 * rb + n, lcol0 / 8 + 4 * h + i);
             const uint4_t wv = *slot;
-            float o[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) o[q] = c * acc[rb][q & 1][4 * (q >> 1) + i];
             uint4_t out;
 #pragma unroll
-            for (int hh = 0; hh < 4; ++hh)
-                out[hh] = pack_bf16_rne(o[2 * hh] + bf16_lo(wv[hh]), o[2 * hh + 1] + bf16_hi(wv[hh]));
+            for (int hh = 0; hh < 4; ++hh)  // one fused multiply-add per element, one rounding to bf16
+                out[hh] = pack_bf16_rne(__builtin_fmaf(c, acc[rb][0][4 * hh + i], bf16_lo(wv[hh])),
+                                        __builtin_fmaf(c, acc[rb][1][4 * hh + i], bf16_hi(wv[hh])));
             *slot = out;
         }
 }
@@ -119,7 +117,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
 
     Terms terms;
     if (!load_terms<NT>(p, terms)) return;
-    const int nt = p.inplace ? (p.mode == 2 ? 2 * p.k : p.k) : p.k;
+    sort_terms_by_magnitude<NT>(terms);  // ascending |c|: every ratio of the accumulator chain has magnitude <= 1
 
     const TileDev tile = p.tiles[blockIdx.x];
     const MatDev m = p.mats[tile.mat];
@@ -151,7 +149,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
     // the thread's BT bytes of a 32-byte piece row; beyond a padded rank: an offset outside the descriptor, which reads as zero
     const uint32_t boff = BT * bpart < 2 * RK ? 2u * (uint32_t)brow * R + 32u * bwhich + (uint32_t)BT * bpart : 0xffffff00u;
     const uint32_t b_bytes = (uint32_t)(m.out - tile.row0) * R * 2u;
-    auto in_use = [&](int step) { return step / KS < nt && terms.c[step / KS] != 0.0f; };
+    auto in_use = [&](int step) { return terms.c[step / KS] != 0.0f; };  // unused slots carry coefficient 0
     auto fetch_b = [&](BPiece &v, int step) {  // the group of pieces that starts at k-step `step`
         const __amdgpu_buffer_rsrc_t rs =
             make_buffer(m.b_bank + ((size_t)terms.e[step / KS] * m.out + tile.row0) * R, in_use(step) ? b_bytes : 0u);
@@ -165,8 +163,15 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
     auto fetch_x = [&](uint4_t (&d)[2], int step) {
         const __amdgpu_buffer_rsrc_t rs = make_buffer(m.a_bank + ((size_t)terms.e[step / KS] * R + 16 * (step % KS)) * m.in,
                                                       in_use(step) ? (uint32_t)RK * in_bytes : 0u);  // rank indices beyond a padded rank read as zero
+        // Zero padding of ranks 4 and 8: the per-lane offset of the upper half (h = 1, 8 rows in) fails
+        // the descriptor's range check and reads as zero.  The uniform offset is not part of that
+        // check, so at rank 4 the second load (rank indices 4..7 of the lower half: the next
+        // expert's rows, or whatever follows the bank) is not issued at all.
         d[0] = ld_buffer_b128(rs, xoff, 0u);
-        d[1] = ld_buffer_b128(rs, xoff, 4u * in_bytes);
+        if constexpr (RK > 4)
+            d[1] = ld_buffer_b128(rs, xoff, 4u * in_bytes);
+        else
+            d[1] = uint4_t{0u, 0u, 0u, 0u};
     };
 
     auto stash_b = [&](const BPiece &v, int slot) {  // the group goes into slots slot .. slot + G - 1
@@ -228,7 +233,7 @@ __global__ __launch_bounds__(64 * NW) void switch_gemm_overlap_kernel(SwitchPara
             if (step % KS == 0 && in_use(step)) {  // a new expert: rescale what is accumulated so far (uniform branch, no loads inside)
                 const float c = terms.c[step / KS];
                 if (c_last != 0.0f) {
-                    const float ratio = c_last / c;
+                    const float ratio = c_last / c;  // |ratio| <= 1
 #pragma unroll
                     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll

@@ -12,14 +12,14 @@ import torch
 
 import adafuse_workloads as wlmod
 import paper_2603_11873_amd as af
-from gpu_util import DeviceModel, Tally, check_full, check_rows, compare, oracle_decisions, sample_rows
+from gpu_util import DeviceModel, Tally, check_full, check_rows, compare, compare_inplace, judge, oracle_decisions, sample_rows
 
 pytestmark = pytest.mark.gpu
 
 ULP_TOL = 1            # bf16 spacings
 LOGIT_RTOL = 1e-5
 GATE_RTOL = 1e-5
-MAX_DIFF_FRACTION = 0.01   # elements allowed to differ at all (near-ties of the rounding)
+MAX_DIFF_FRACTION = 1e-4   # elements allowed to differ at all (near-ties of the rounding; measured 1e-5)
 
 KERNELS = [af.KERNEL_VALU, af.KERNEL_MFMA]
 ALL_KERNELS = KERNELS + [af.KERNEL_GEMM]
@@ -30,6 +30,9 @@ def _sync():
 
 
 def _compare_pregate(oracle, hidden, router, k, norm):
+    """Logits within 1e-5 of the token's largest, indices bit-exact on EVERY token, gates within
+    1e-5 relative.  (The workload generators redraw near-tie tokens, and the hand-made inputs of
+    the other tests are seeded, so the decision is well defined on both sides.)"""
     idx, gates, logits = af.pregate(hidden, router, k, norm)
     _sync()
     ref = oracle.pregate(wlmod.bits(hidden), wlmod.bits(router), k, norm)
@@ -37,29 +40,21 @@ def _compare_pregate(oracle, hidden, router, k, norm):
     scale = np.abs(ref["logits"]).max(axis=1, keepdims=True)
     # relative to the token's largest logit: a logit that happens to be ~0 has no relative accuracy in any arithmetic
     assert np.all(np.abs(lg - ref["logits"]) <= LOGIT_RTOL * scale)
-    # fp64 accumulation on the device: the fp32 logits normally agree to the bit
-    assert np.mean(logits.cpu().numpy() != ref["logits32"]) < 1e-3
-    got_idx = idx.cpu().numpy()
-    # tokens whose fp32 logits are not all distinct near the selection boundary are still uniquely
-    # ordered by the index rule; a token is exempt from bit-exactness only if the two sides' fp32
-    # logits differ (then both orders are valid for their own logits)
-    same_logits = np.all(logits.cpu().numpy() == ref["logits32"], axis=1)
-    assert np.array_equal(got_idx[same_logits], ref["idx"][same_logits])
-    for t in np.nonzero(~same_logits)[0]:
-        order = np.argsort(-lg[t], kind="stable")[:k]
-        assert np.array_equal(got_idx[t], order)
+    assert np.array_equal(idx.cpu().numpy(), ref["idx"])
     g = gates.cpu().numpy().astype(np.float64)
-    ok = same_logits
-    assert np.all(np.abs(g[ok] - ref["gates"][ok]) <= GATE_RTOL * ref["gates"][ok])
+    assert np.all(np.abs(g - ref["gates"]) <= GATE_RTOL * ref["gates"])
     return idx, gates, ref
 
 
-@pytest.mark.parametrize("name", ["toy", "llama2_7b_attn", "llama3_8b_gqa_all", "llama2_13b_all"])
+@pytest.mark.parametrize("name", wlmod.ORDER)
 @pytest.mark.parametrize("norm", [0, 1])
-def test_pregate_matches_oracle(oracle, name, norm):
+@pytest.mark.parametrize("gen_device", ["cpu", "cuda"])
+def test_pregate_matches_oracle(oracle, name, norm, gen_device):
+    """All five configurations, every token of the sequence, on the inputs the CPU tests draw and
+    on the ones the bench and the full-size tests draw (torch's generators differ per device)."""
     wl = wlmod.WORKLOADS[name]
-    hidden = wlmod.gen_hidden(wl).cuda()
-    router = wlmod.gen_router(wl).cuda()
+    hidden = wlmod.gen_hidden(wl, gen_device).cuda()
+    router = wlmod.gen_router(wl, gen_device).cuda()
     _compare_pregate(oracle, hidden, router, wl.k, norm)
 
 
@@ -125,11 +120,10 @@ def test_invariants_on_device(oracle, kernel):
     m.ctx.fused_switch(None, None, e2, one, 1, wl.scale, af.MERGE)
     _sync()
     for wb, ww, a, b in m.mats:
-        ref = wb.double().cpu().numpy() + wl.scale * (b[2].double().cpu().numpy() @ a[2].double().cpu().numpy())
-        mx, nd = oracle.ulp_diff(wlmod.bits(ww), oracle.f64_to_bf16(ref))
-        if mx > ULP_TOL:   # only a cancellation case may exceed it; compare() judges those
-            Tally().add(compare(oracle, wlmod.bits(wb), wlmod.bits(a), wlmod.bits(b), wlmod.bits(ww), [2], [1.0],
-                                wl.scale), ULP_TOL)
+        W, B2, A2 = wb.double().cpu().numpy(), b[2].double().cpu().numpy(), a[2].double().cpu().numpy()
+        ref = W + wl.scale * (B2 @ A2)
+        mag = np.abs(W) + wl.scale * (np.abs(B2) @ np.abs(A2))
+        Tally().add(judge(wlmod.bits(ww), oracle.f64_to_bf16(ref), lambda: (ref, mag), wl.r + 3), ULP_TOL)
     # SWAP with prev bit-identical to next must not touch W_work
     g = torch.tensor([0.25, 0.75], dtype=torch.float32, device=dev)
     m.ctx.fused_switch(None, None, idx, g, 2, wl.scale, af.MERGE)
@@ -271,10 +265,13 @@ def test_fewer_experts_than_the_context_allows(oracle, kernel, r):
 
 
 @pytest.mark.parametrize("kernel", ALL_KERNELS)
-def test_one_full_layer_of_the_7b_shape(oracle, kernel):
-    """Every element of the seven matrices of one Llama-2-7B-shaped layer (several
-    hundred tiles per matrix, 11008 is not a multiple of the tile height)."""
-    wl = wlmod.scaled_down(wlmod.WORKLOADS["llama2_7b_all"], 1)
+@pytest.mark.parametrize("name", ["llama2_7b_all", "llama3_8b_gqa_all", "llama2_13b_all"])
+def test_one_full_layer_every_element(oracle, kernel, name):
+    """Every element of the seven matrices of one full-size layer of each Llama shape (several
+    hundred tiles per matrix; 11008 is not a multiple of the tile height; the 8B shape takes the
+    four-term form with its operands requested first; the 13B shape has row pitches of 10240 and
+    27648 bytes)."""
+    wl = wlmod.scaled_down(wlmod.WORKLOADS[name], 1)
     m = DeviceModel(wl, gen_device="cuda")
     m.ctx.set_kernel(kernel)
     hi, hgs, idx, gates = oracle_decisions(oracle, m.hidden, m.router, wl.k)
@@ -286,7 +283,7 @@ def test_one_full_layer_of_the_7b_shape(oracle, kernel):
     for mat in m.mats:
         tally.add(check_full(oracle, mat, hidx, hg, wl.scale), ULP_TOL)
     tally.finish(MAX_DIFF_FRACTION)
-    print(f"\n[{kernel}] elements {tally.n}, differing from oracle {tally.diff}, cancellation cases {tally.cancel}")
+    print(f"\n[{name}, kernel {kernel}] {tally.summary()}")
     m.close()
 
 
@@ -326,7 +323,7 @@ def test_full_size_models_sampled_rows(oracle, name):
             rows = sample_rows(mat[0].shape[0], info.tile_rows, rng)
             tally.add(check_rows(oracle, mat, hidx[t], hg[t], wl.scale, rows), ULP_TOL, (name, t))
     tally.finish(MAX_DIFF_FRACTION)
-    print(f"\n[{name}] sampled elements {tally.n}, differing {tally.diff}, cancellation cases {tally.cancel}")
+    print(f"\n[{name}] sampled {tally.summary()}")
     # nothing left unwritten anywhere: no element still holds the NaN sentinel
     for _, ww, _, _ in m.mats[:: max(1, len(m.mats) // 16)]:
         assert not bool((ww.view(torch.int16) == 0x7FC1).any())
@@ -353,7 +350,7 @@ def test_full_size_models_every_element(oracle, name):
             print(f"[{name}] matrix {mi + 1} of {len(m.mats)}: {tally.n} elements so far, differing {tally.diff}", flush=True)
     tally.finish(MAX_DIFF_FRACTION)
     assert tally.n == wl.elements
-    print(f"\n[{name}] ALL {tally.n} elements, differing {tally.diff}, cancellation cases {tally.cancel}")
+    print(f"\n[{name}] ALL {tally.summary()}")
     m.close()
 
 
@@ -374,31 +371,7 @@ def _inplace_model(wl, k_max=None):
 def _check_inplace_step(oracle, before, mat, prev, nxt, scale):
     """One in-place call against the oracle's single-rounded Eq.8 step from the same bits."""
     _, w, a, b = mat
-    want = oracle.inplace_swap(before, wlmod.bits(a), wlmod.bits(b), prev[0], prev[1], nxt[0], nxt[1], scale)
-    got = wlmod.bits(w)
-    mx, nd = oracle.ulp_diff(got, want)
-    if mx > ULP_TOL:
-        # only a cancellation may exceed one spacing (same derived bar as gpu_util.compare,
-        # with the previous token's terms counted too)
-        to_f = lambda x: wlmod.from_bits(x).double().numpy()
-        A, B = to_f(wlmod.bits(a)), to_f(wlmod.bits(b))
-        exact = to_f(before)
-        mag = np.abs(exact)
-        n_terms = 0
-        for sign, (ids, gs) in ((-1, prev), (1, nxt)):
-            for e, g in zip(ids, gs):
-                exact = exact + sign * scale * float(g) * (B[e] @ A[e])
-                mag = mag + abs(scale * float(g)) * (np.abs(B[e]) @ np.abs(A[e]))
-                n_terms += 1
-        gv, wv = to_f(got), to_f(want)
-        spacing = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(wv), 2.0 ** -126))) - 7)
-        line = lambda x: np.where(x.astype(np.int32) & 0x8000, -(x.astype(np.int32) & 0x7FFF), x.astype(np.int32))
-        over = np.abs(line(got) - line(want)) > ULP_TOL
-        bound = 0.5 * spacing + (a.shape[1] + n_terms + 2) * 2.0 ** -24 * mag
-        assert np.all(np.abs(gv - exact)[over] <= bound[over]), "in-place step outside both bars"
-        assert np.all(np.abs(exact)[over] < 2.0 ** -8 * mag[over])
-        assert np.count_nonzero(over) <= max(2, 1e-5 * over.size)
-    return nd, want.size
+    return compare_inplace(oracle, before, wlmod.bits(a), wlmod.bits(b), wlmod.bits(w), prev, nxt, scale)
 
 
 @pytest.mark.parametrize("kernel", ALL_KERNELS)
@@ -413,7 +386,7 @@ def test_inplace_steps_match_oracle(oracle, kernel):
     hidx, hg, idx, gates = oracle_decisions(oracle, hidden, router, wl.k)
     empty = (np.zeros(0, np.int32), np.zeros(0, np.float32))
     host = [(wlmod.bits(wb), wlmod.bits(m[2]), wlmod.bits(m[3])) for wb, m in zip(base, mats)]
-    diff = total = 0
+    tally = Tally()
     for t in range(wl.T):
         prev = (hidx[t - 1], hg[t - 1]) if t else empty
         before = [oracle.merge(w, a, b, prev[0], prev[1], wl.scale) for w, a, b in host]
@@ -425,10 +398,7 @@ def test_inplace_steps_match_oracle(oracle, kernel):
             ctx.fused_switch(idx[t - 1], gates[t - 1], idx[t], gates[t], wl.k, wl.scale, af.SWAP)
         _sync()
         for mat, bf in zip(mats, before):
-            nd, n = _check_inplace_step(oracle, bf, mat, prev, (hidx[t], hg[t]), wl.scale)
-            diff += nd
-            total += n
-    assert diff <= MAX_DIFF_FRACTION * total
+            tally.add(_check_inplace_step(oracle, bf, mat, prev, (hidx[t], hg[t]), wl.scale), ULP_TOL, t)
     # un-merge in place is arithmetic: W - dW(prev), not a copy of the base
     t = wl.T - 1
     before = [oracle.merge(w, a, b, hidx[t], hg[t], wl.scale) for w, a, b in host]
@@ -437,7 +407,8 @@ def test_inplace_steps_match_oracle(oracle, kernel):
     ctx.fused_switch(idx[t], gates[t], None, None, wl.k, wl.scale, af.UNMERGE)
     _sync()
     for mat, bf in zip(mats, before):
-        _check_inplace_step(oracle, bf, mat, (hidx[t], hg[t]), empty, wl.scale)
+        tally.add(_check_inplace_step(oracle, bf, mat, (hidx[t], hg[t]), empty, wl.scale), ULP_TOL, "unmerge")
+    tally.finish(MAX_DIFF_FRACTION)
     # same decision twice: exactly-zero update, W untouched
     snap = [m[1].clone() for m in mats]
     ctx.fused_switch(idx[3], gates[3], idx[3].clone(), gates[3].clone(), wl.k, wl.scale, af.SWAP)
@@ -471,7 +442,7 @@ def test_inplace_experts_common_to_both_tokens(oracle, kernel):
                          wl.k, wl.scale, af.SWAP)
         _sync()
         for mat, bf in zip(mats, before):
-            _check_inplace_step(oracle, bf, mat, prev, nxt, wl.scale)
+            Tally().add(_check_inplace_step(oracle, bf, mat, prev, nxt, wl.scale), ULP_TOL, (pi, ni))
             if frozen:
                 assert np.array_equal(wlmod.bits(mat[1]), bf)
     ctx.close()
@@ -550,14 +521,12 @@ def test_inplace_full_layer(oracle, name):
         before[mi] = merged
     ctx.fused_switch(idx[0], gates[0], idx[1], gates[1], wl.k, wl.scale, af.SWAP)
     _sync()
-    diff = total = 0
+    tally = Tally()
     for mi, m in enumerate(mats):
         ridx = torch.as_tensor(rows[mi], device=dev)
         sub = (None, m[1].index_select(0, ridx), m[2], m[3].index_select(1, ridx))
-        nd, n = _check_inplace_step(oracle, before[mi], sub, (hidx[0], hg[0]), (hidx[1], hg[1]), wl.scale)
-        diff += nd
-        total += n
-    assert diff <= MAX_DIFF_FRACTION * total
+        tally.add(_check_inplace_step(oracle, before[mi], sub, (hidx[0], hg[0]), (hidx[1], hg[1]), wl.scale), ULP_TOL, mi)
+    tally.finish(MAX_DIFF_FRACTION)
     ctx.close()
 
 
@@ -644,7 +613,7 @@ def test_rank_looped_kernel_modes(oracle, r, k, inplace):
         ctx.fused_switch(di0, dg0, di1, dg1, k, 2.0, af.SWAP)
         _sync()
         for m, bf in zip(mats, before):
-            _check_inplace_step(oracle, bf, m, (i0, g0), (i1, g1), 2.0)
+            tally.add(_check_inplace_step(oracle, bf, m, (i0, g0), (i1, g1), 2.0), ULP_TOL)
     else:
         ctx.fused_switch(di0, dg0, di1, dg1, k, 2.0, af.SWAP)
         _sync()
