@@ -240,6 +240,21 @@ adafuse_status adafuse_forward_merged(adafuse_ctx *ctx, const void *x, float *y,
 adafuse_status adafuse_forward_dynamic(adafuse_ctx *ctx, const int32_t *idx, const float *gates, int32_t k,
                                        float scale, const void *x, float *y, float *z, void *hip_stream);
 
+/*
+ * adafuse_forward_dynamic for callers that cannot allocate device memory or hand over a
+ * workspace (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the same launches and the same result, with the down-projected activations z
+ * held in a scratch array built into the library (1024 floats = 4 KB per GPU, resident until
+ * the process ends) instead of a caller buffer.  The call allocates nothing and frees nothing.
+ * k * r <= 1024, else ERR_ARG (every (k <= 8, r <= 128) a context accepts fits).  All calls on
+ * one GPU share that array: two calls that may run at the same time (different streams, or
+ * different host threads) race on it and must be ordered by the caller.  Nothing in it has
+ * to start at zero; each call overwrites what it reads.  Other errors as
+ * adafuse_forward_dynamic.
+ */
+adafuse_status adafuse_forward_dynamic_static(adafuse_ctx *ctx, const int32_t *idx, const float *gates, int32_t k,
+                                              float scale, const void *x, float *y, void *hip_stream);
+
 const char *adafuse_status_string(int32_t status);
 
 #ifdef __cplusplus

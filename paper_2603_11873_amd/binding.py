@@ -12,7 +12,7 @@ KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_GEMM = 0, 1, 2, 3
 
 EXPORTS = ["adafuse_create", "adafuse_destroy", "adafuse_set_kernel", "adafuse_get_info",
            "adafuse_pregate", "adafuse_fused_switch", "adafuse_switch_per_matrix", "adafuse_forward_merged", "adafuse_forward_dynamic",
-           "adafuse_switch_kernel_name", "adafuse_status_string"]
+           "adafuse_forward_dynamic_static", "adafuse_switch_kernel_name", "adafuse_status_string"]
 
 
 class AdafuseError(RuntimeError):
@@ -67,6 +67,8 @@ def load_library():
     L.adafuse_forward_merged.argtypes = [vp, vp, vp, vp]
     L.adafuse_forward_dynamic.restype = i32
     L.adafuse_forward_dynamic.argtypes = [vp, C.POINTER(i32), C.POINTER(f32), i32, f32, vp, vp, vp, vp]
+    L.adafuse_forward_dynamic_static.restype = i32
+    L.adafuse_forward_dynamic_static.argtypes = [vp, C.POINTER(i32), C.POINTER(f32), i32, f32, vp, vp, vp]
     L.adafuse_switch_kernel_name.restype = C.c_char_p
     L.adafuse_switch_kernel_name.argtypes = [vp, i32, i32]
     L.adafuse_status_string.restype = C.c_char_p
@@ -188,6 +190,16 @@ class Context:
                                                     _stream_handle(stream))
         if st != 0:
             raise AdafuseError(st, "adafuse_forward_dynamic")
+
+    def forward_dynamic_static(self, idx, gates, scale, x, y, stream=None):
+        """adafuse_forward_dynamic_static: forward_dynamic with the library's built-in scratch (no workspace)."""
+        k = len(idx)
+        ci = (C.c_int32 * k)(*[int(v) for v in idx])
+        cg = (C.c_float * k)(*[float(v) for v in gates])
+        st = load_library().adafuse_forward_dynamic_static(self._h, ci, cg, k, scale, _ptr(x), _ptr(y),
+                                                           _stream_handle(stream))
+        if st != 0:
+            raise AdafuseError(st, "adafuse_forward_dynamic_static")
 
     def close(self):
         if self._h:

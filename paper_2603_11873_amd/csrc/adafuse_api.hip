@@ -19,6 +19,14 @@
 
 using namespace adafuse;
 
+// Scratch of adafuse_forward_dynamic_static: the down-projected activations z (k x r floats)
+// that adafuse_forward_dynamic takes as a caller workspace.  One copy per GPU, held until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress: the device
+// address is looked up once per context (build_tables, with the context's device current) and
+// kept in adafuse_ctx::scratch, which is what the launches pass.
+constexpr int kScratchFloats = 1024;  // k * r <= 8 * 128
+static __device__ __align__(256) float scratch[kScratchFloats];
+
 struct adafuse_ctx {
     std::vector<adafuse_matrix_desc> mats;
     int32_t E = 0, r = 0, k_max = 0;
@@ -30,6 +38,7 @@ struct adafuse_ctx {
     int32_t order = 1;       // tiles per XCD run (ADAFUSE_ORDER; 0 = plain order, 1 = an eighth of the list)
     int64_t n_tiles = 0, elements = 0;
     int device = -1;
+    float *scratch = nullptr;            // this device's copy of the file-scope scratch array
     MatDev *d_mats = nullptr;
     TileDev *d_tiles = nullptr;          // [0, n_tiles): whole model; [n_tiles, 2 n_tiles): matrix by matrix
     std::vector<int64_t> mat_tile_off;   // per-matrix ranges inside the second section (n_mats + 1 entries)
@@ -358,6 +367,8 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
 
     int device = -1;
     if (hipGetDevice(&device) != hipSuccess) return ADAFUSE_ERR_HIP;
+    void *scratch_ptr = nullptr;  // each GPU holds its own copy of the array, at its own address
+    if (hipGetSymbolAddress(&scratch_ptr, HIP_SYMBOL(scratch)) != hipSuccess || !scratch_ptr) return ADAFUSE_ERR_HIP;
     MatDev *dm = nullptr;
     TileDev *dt = nullptr;
     if (hipMalloc(&dm, hm.size() * sizeof(MatDev)) != hipSuccess) return ADAFUSE_ERR_HIP;
@@ -375,6 +386,7 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
     c->d_mats = dm;
     c->d_tiles = dt;
     c->device = device;
+    c->scratch = static_cast<float *>(scratch_ptr);
     c->kernel = kernel;
     c->mfma_shape = mfma_shape;
     c->gemm_waves = gemm_waves;
@@ -559,16 +571,11 @@ adafuse_status adafuse_forward_merged(adafuse_ctx *ctx, const void *x, float *y,
     return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
 }
 
-adafuse_status adafuse_forward_dynamic(adafuse_ctx *ctx, const int32_t *idx_host, const float *gates_host, int32_t k,
-                                       float scale, const void *x, float *y, float *z, void *hip_stream)
+namespace {
+
+adafuse_status forward_dynamic_launches(adafuse_ctx *ctx, const int32_t *idx_host, const float *gates_host, int32_t k,
+                                        float scale, const void *x, float *y, float *z, void *hip_stream)
 {
-    if (!ctx || !idx_host || !gates_host || !x || !y || !z) return ADAFUSE_ERR_NULL;
-    if (k < 1 || k > ctx->k_max) return ADAFUSE_ERR_ARG;
-    for (int j = 0; j < k; ++j)
-        if (idx_host[j] < 0 || idx_host[j] >= ctx->E) return ADAFUSE_ERR_ARG;
-    if (ctx->inplace) return ADAFUSE_ERR_ARG;  // needs the unmodified base weights
-    if (!aligned16(x)) return ADAFUSE_ERR_ALIGN;
-    if (!on_ctx_device(ctx)) return ADAFUSE_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const uint16_t *xp = static_cast<const uint16_t *>(x);
     const int r = ctx->r;
@@ -587,6 +594,41 @@ adafuse_status adafuse_forward_dynamic(adafuse_ctx *ctx, const int32_t *idx_host
         y += m.out;
     }
     return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
+}
+
+adafuse_status forward_dynamic_checks(adafuse_ctx *ctx, const int32_t *idx_host, const float *gates_host, int32_t k,
+                                      const void *x, float *y)
+{
+    if (!ctx || !idx_host || !gates_host || !x || !y) return ADAFUSE_ERR_NULL;
+    if (k < 1 || k > ctx->k_max) return ADAFUSE_ERR_ARG;
+    for (int j = 0; j < k; ++j)
+        if (idx_host[j] < 0 || idx_host[j] >= ctx->E) return ADAFUSE_ERR_ARG;
+    if (ctx->inplace) return ADAFUSE_ERR_ARG;  // needs the unmodified base weights
+    if (!aligned16(x)) return ADAFUSE_ERR_ALIGN;
+    if (!on_ctx_device(ctx)) return ADAFUSE_ERR_ARG;
+    return ADAFUSE_OK;
+}
+
+}  // namespace
+
+adafuse_status adafuse_forward_dynamic(adafuse_ctx *ctx, const int32_t *idx_host, const float *gates_host, int32_t k,
+                                       float scale, const void *x, float *y, float *z, void *hip_stream)
+{
+    if (!z) return ADAFUSE_ERR_NULL;
+    const adafuse_status st = forward_dynamic_checks(ctx, idx_host, gates_host, k, x, y);
+    if (st != ADAFUSE_OK) return st;
+    return forward_dynamic_launches(ctx, idx_host, gates_host, k, scale, x, y, z, hip_stream);
+}
+
+adafuse_status adafuse_forward_dynamic_static(adafuse_ctx *ctx, const int32_t *idx_host, const float *gates_host,
+                                              int32_t k, float scale, const void *x, float *y, void *hip_stream)
+{
+    const adafuse_status st = forward_dynamic_checks(ctx, idx_host, gates_host, k, x, y);
+    if (st != ADAFUSE_OK) return st;
+    if ((int64_t)k * ctx->r > kScratchFloats) return ADAFUSE_ERR_ARG;  // beyond the built-in scratch
+    // every entry of z that a launch reads was written by the launch before it on the same stream:
+    // nothing of the previous call's contents is used, nothing has to be cleared
+    return forward_dynamic_launches(ctx, idx_host, gates_host, k, scale, x, y, ctx->scratch, hip_stream);
 }
 
 const char *adafuse_switch_kernel_name(const adafuse_ctx *ctx, int32_t k, int32_t mode)
