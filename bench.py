@@ -51,15 +51,27 @@ def parse_args():
 
 
 def read_traffic(workload, kernel_fn):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this kernel and workload, if there is one."""
-    path = os.path.join(ROOT, "profiles", f"{kernel_fn.replace('_kernel', '')}_{workload}_pmc.txt")
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this kernel and workload.
+
+    The counters cannot be read inside a timed run, so the figure is a stored measurement; it is
+    only reported while the library's sources still hash to the stamp the summary carries.
+    Returns (bytes or None, note)."""
+    from paper_2603_11873_amd.build import source_hash
+    name = f"{kernel_fn.replace('_kernel', '')}_{workload}_pmc.txt"
+    path = os.path.join(ROOT, "profiles", name)
+    traffic = stamp = None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+                traffic = float(line.split(":")[1])
+            elif line.startswith("csrc_sha16:"):
+                stamp = line.split(":")[1].strip()
     except OSError:
-        pass
-    return None
+        return None, f"no counter summary profiles/{name}"
+    now = source_hash()
+    if stamp != now:
+        return None, f"traffic_stale: profiles/{name} was measured on sources {stamp}, the library is built from {now}"
+    return traffic, f"rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/{name}, sources {stamp}"
 
 
 def cpu_baseline(wl, mats, hidden, router, t, n_layers):
@@ -207,6 +219,8 @@ def main():
     # the second bound: 2 k r flops per element of the low-rank product (twice that in place), against the dense bf16 MFMA peak
     alg_flops = 0 if mode != af.SWAP and not args.inplace else wl.flops * (2 if args.inplace and mode == af.SWAP else 1)
     srt = sorted(kernel_ms)
+    traffic, traffic_note = (read_traffic(wl.name, ctx.switch_kernel_name(wl.k, mode))
+                             if mode == af.SWAP and not args.inplace else (None, "not measured for this mode"))
 
     out = {
         "metric": "fused-switch latency per token, all layers (us) + achieved HBM GB/s vs peak",
@@ -228,7 +242,7 @@ def main():
                    "step": "pregate(1 token) + fused_switch(all matrices), one stream"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": read_traffic(wl.name, ctx.switch_kernel_name(wl.k, mode)) if mode == af.SWAP and not args.inplace else None,
+                     "traffic": traffic, "traffic_source": traffic_note,
                      "kernel": ctx.switch_kernel_name(wl.k, mode),
                      "algorithmic_bytes_per_launch": alg_bytes, "early_out_launches_excluded": early_outs,
                      "matrix_core": {"achieved": alg_flops / avg_kernel_s / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -237,6 +251,12 @@ def main():
                      "kernel_us": {"mean": avg_kernel_s * 1e6, "median": srt[len(srt) // 2] * 1e3,
                                    "p95": srt[int(0.95 * (len(srt) - 1))] * 1e3, "min": srt[0] * 1e3}},
     }
+    if args.steps >= T:
+        # one full pass over the token sequence (the first T timed launches), launch by launch
+        seq = sorted(a.elapsed_time(b) * 1e3 for a, b in events[:T])
+        out["roofline"]["kernel_us_one_sequence"] = {
+            "tokens": T, "median": seq[len(seq) // 2], "mean": sum(seq) / len(seq), "p95": seq[int(0.95 * (len(seq) - 1))],
+            "min": seq[0], "max": seq[-1]}
     if args.graph:
         # the same T steps as one graph: no per-launch host cost between the kernels
         graph = torch.cuda.CUDAGraph()

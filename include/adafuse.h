@@ -28,7 +28,7 @@
  *
  * Threads: a context is not locked.  Calls that only enqueue (pregate, the
  * switches, the forward passes, get_info, switch_kernel_name) may run from
- * several host threads at once; adafuse_set_kernel and adafuse_destroy must not
+ * several host threads at once; adafuse_set_option and adafuse_destroy must not
  * overlap with any other call on the same context.  Two switches on the same
  * context write the same W_work: order them on one stream (or with events)
  * like any other pair of kernels that write the same memory.
@@ -128,11 +128,27 @@ adafuse_status adafuse_create(const adafuse_matrix_desc *mats, int32_t n_mats,
 /* Free the context's tables.  NULL is accepted.  Caller buffers are untouched. */
 adafuse_status adafuse_destroy(adafuse_ctx *ctx);
 
-/* Choose the switch kernel (adafuse_kernel).  Rebuilds the tile table if the
- * tile shape changes (allocates and synchronises like adafuse_create; the
- * context's device must be current, else ERR_ARG).  On any error the context
- * keeps the kernel and tables it had. */
-adafuse_status adafuse_set_kernel(adafuse_ctx *ctx, int32_t kernel);
+/*
+ * Options of a context, all with a default the library chooses by itself.  They exist for
+ * measurements (baselines, ablations); a serving caller needs none of them.
+ */
+typedef enum {
+    ADAFUSE_OPT_KERNEL = 0,     /* adafuse_kernel; AUTO = the library's choice for (r, k_max) */
+    ADAFUSE_OPT_GEMM_WAVES = 1, /* waves per workgroup of ADAFUSE_KERNEL_GEMM (tile 64 x 64 waves): 4, 8, or 0 =
+                                   chosen from the matrices' row pitches */
+    ADAFUSE_OPT_GEMM_FORM = 2,  /* form of ADAFUSE_KERNEL_GEMM: 0 = by the length of the contraction, 1 = unrolled,
+                                   3 = overlapped with the W fetch, wherever that form can take the launch */
+    ADAFUSE_OPT_XCD_RUN = 3,    /* tile order: 0 = plain, 1 = one contiguous eighth of the tile list per XCD
+                                   (default), G > 1 = runs of G tiles per XCD */
+    ADAFUSE_OPT_PANEL_KB = 4,   /* column-operand budget of a column panel in KiB (default 2048) */
+    ADAFUSE_OPT_MFMA_SHAPE = 5  /* tile shape of ADAFUSE_KERNEL_MFMA: 0..5, -1 = the library's choice */
+} adafuse_option;
+
+/* Set one option.  Rebuilds the tile table (allocates and synchronises like
+ * adafuse_create; the context's device must be current, else ERR_ARG).  Unknown
+ * option or value out of range -> ERR_ARG.  On any error the context keeps the
+ * kernel, tables and options it had. */
+adafuse_status adafuse_set_option(adafuse_ctx *ctx, int32_t option, int32_t value);
 
 /* Fill *info (HOST) with the context's geometry. */
 adafuse_status adafuse_get_info(const adafuse_ctx *ctx, adafuse_info *info);

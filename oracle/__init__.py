@@ -11,7 +11,7 @@ import os
 
 import numpy as np
 
-from .build import build as _build
+from .build import build as _build, build_ubsan as _build_ubsan
 
 _lib = None
 
@@ -26,7 +26,7 @@ def lib():
     """Load (building with gcc if needed) the oracle shared library."""
     global _lib
     if _lib is None:
-        path = _build()
+        path = _build_ubsan() if os.environ.get("ADAFUSE_ORACLE_UBSAN") == "1" else _build()
         L = C.CDLL(path)
         L.oracle_bf16_to_f64.restype = C.c_double
         L.oracle_bf16_to_f64.argtypes = [C.c_uint16]

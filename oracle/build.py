@@ -19,5 +19,17 @@ def build(force: bool = False) -> str:
     return LIB
 
 
+def build_ubsan() -> str:
+    """The same source with the undefined-behaviour sanitizer compiled in (aborts on the first
+    finding), as oracle/liboracle_ubsan.so: lib() loads it instead when ADAFUSE_ORACLE_UBSAN=1,
+    so the whole pin suite can be run once against it."""
+    lib = os.path.join(HERE, "liboracle_ubsan.so")
+    cmd = ["gcc", "-O1", "-g", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-fno-fast-math",
+           "-fsanitize=undefined", "-fno-sanitize-recover=all", "-Wall", "-Wextra", "-o", lib + ".tmp", SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    os.replace(lib + ".tmp", lib)
+    return lib
+
+
 if __name__ == "__main__":
     print(build(force="--force" in sys.argv))

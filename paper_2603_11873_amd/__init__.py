@@ -13,6 +13,12 @@ from .binding import (  # noqa: F401
     KERNEL_MFMA,
     KERNEL_VALU,
     MERGE,
+    OPT_GEMM_FORM,
+    OPT_GEMM_WAVES,
+    OPT_KERNEL,
+    OPT_MFMA_SHAPE,
+    OPT_PANEL_KB,
+    OPT_XCD_RUN,
     SWAP,
     UNMERGE,
     AdafuseError,

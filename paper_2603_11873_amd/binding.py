@@ -9,8 +9,9 @@ _lib = None
 MERGE, UNMERGE, SWAP = 0, 1, 2
 GATE_SOFTMAX_OVER_TOPK, GATE_TOPK_OF_SOFTMAX = 0, 1
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_GEMM = 0, 1, 2, 3
+OPT_KERNEL, OPT_GEMM_WAVES, OPT_GEMM_FORM, OPT_XCD_RUN, OPT_PANEL_KB, OPT_MFMA_SHAPE = range(6)
 
-EXPORTS = ["adafuse_create", "adafuse_destroy", "adafuse_set_kernel", "adafuse_get_info",
+EXPORTS = ["adafuse_create", "adafuse_destroy", "adafuse_set_option", "adafuse_get_info",
            "adafuse_pregate", "adafuse_fused_switch", "adafuse_switch_per_matrix", "adafuse_forward_merged", "adafuse_forward_dynamic",
            "adafuse_forward_dynamic_static", "adafuse_switch_kernel_name", "adafuse_status_string"]
 
@@ -53,8 +54,8 @@ def load_library():
     L.adafuse_create.argtypes = [C.POINTER(MatrixDesc), i32, i32, i32, i32, C.POINTER(vp)]
     L.adafuse_destroy.restype = i32
     L.adafuse_destroy.argtypes = [vp]
-    L.adafuse_set_kernel.restype = i32
-    L.adafuse_set_kernel.argtypes = [vp, i32]
+    L.adafuse_set_option.restype = i32
+    L.adafuse_set_option.argtypes = [vp, i32, i32]
     L.adafuse_get_info.restype = i32
     L.adafuse_get_info.argtypes = [vp, C.POINTER(Info)]
     L.adafuse_pregate.restype = i32
@@ -144,10 +145,15 @@ class Context:
         if st != 0:
             raise AdafuseError(st, "adafuse_create")
 
-    def set_kernel(self, kernel):
-        st = load_library().adafuse_set_kernel(self._h, kernel)
+    def set_option(self, option, value):
+        """adafuse_set_option"""
+        st = load_library().adafuse_set_option(self._h, option, value)
         if st != 0:
-            raise AdafuseError(st, "adafuse_set_kernel")
+            raise AdafuseError(st, "adafuse_set_option")
+
+    def set_kernel(self, kernel):
+        """adafuse_set_option(ADAFUSE_OPT_KERNEL, kernel)"""
+        self.set_option(OPT_KERNEL, kernel)
 
     def info(self) -> Info:
         info = Info()

@@ -10,6 +10,20 @@ LIB = os.path.join(PKG, "libadafuse.so")
 SOURCES = [os.path.join(CSRC, "adafuse_api.hip")]
 
 
+def source_hash() -> str:
+    """First 16 hex digits of the SHA-256 over the library's sources (csrc/ and the public header),
+    file names included: the stamp that ties a stored counter measurement to the kernels it was
+    taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".hpp")))
+    for path in files + [os.path.join(ROOT, "include", "adafuse.h")]:
+        h.update(os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
 def build(verbose: bool = False) -> str:
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            # keep the compiler from forming packed fp32 ALU ops

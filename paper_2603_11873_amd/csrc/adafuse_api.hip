@@ -5,11 +5,11 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <cstdlib>
 #include <new>
 #include <vector>
 
 #include "device_types.hpp"
+#include "host_tables.hpp"
 #include "forward.hpp"
 #include "pregate.hpp"
 #include "switch_gemm.hpp"
@@ -32,10 +32,11 @@ struct adafuse_ctx {
     int32_t E = 0, r = 0, k_max = 0;
     int32_t kernel = ADAFUSE_KERNEL_VALU;  // kernel in effect, never AUTO
     int32_t tile_rows = 0, tile_cols = 0;
-    int32_t mfma_shape = 0;  // index into the matrix-core kernel's tile shapes
-    int32_t gemm_waves = 4;  // waves per workgroup of the rank-looped kernel: tile 64 x (64 waves)
+    int32_t mfma_shape = 0;  // tile shape of the 4x4x4 kernel in effect
+    int32_t gemm_waves = 4;  // waves per workgroup of the rank-looped kernel in effect: tile 64 x (64 waves)
     bool inplace = false;    // every matrix has w_work == w_base
-    int32_t order = 1;       // tiles per XCD run (ADAFUSE_ORDER; 0 = plain order, 1 = an eighth of the list)
+    // what adafuse_set_option asked for (0 / -1 = the library chooses)
+    int32_t opt_waves = 0, opt_form = 0, opt_xcd_run = 1, opt_panel_kb = 2048, opt_mfma_shape = -1;
     int64_t n_tiles = 0, elements = 0;
     int device = -1;
     float *scratch = nullptr;            // this device's copy of the file-scope scratch array
@@ -46,7 +47,7 @@ struct adafuse_ctx {
 
 namespace {
 
-bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+using host::aligned16;
 
 int terms_bucket(int k) { return k <= 1 ? 1 : (k <= 2 ? 2 : (k <= 4 ? 4 : 8)); }
 
@@ -57,27 +58,6 @@ bool mfma_supported(int r, int max_terms)
 {
     if (r != 4 && r != 8 && r != 16 && r != 32 && r != 64) return false;
     return max_terms <= kMaxTerms && terms_bucket(max_terms) * r <= 128;
-}
-
-adafuse_status validate_mats(const adafuse_matrix_desc *mats, int32_t n_mats, int32_t E, int32_t r, int32_t k_max)
-{
-    if (!mats) return ADAFUSE_ERR_NULL;
-    if (n_mats < 1 || n_mats > 65535) return ADAFUSE_ERR_ARG;
-    if (E < 1 || E > kMaxExperts) return ADAFUSE_ERR_ARG;
-    if (r != 4 && r != 8 && r != 16 && r != 32 && r != 64 && r != 128) return ADAFUSE_ERR_ARG;
-    if (k_max < 1 || k_max > E || k_max > kMaxTerms) return ADAFUSE_ERR_ARG;
-    for (int32_t i = 0; i < n_mats; ++i) {
-        const adafuse_matrix_desc &m = mats[i];
-        if (!m.w_base || !m.w_work || !m.a_bank || !m.b_bank) return ADAFUSE_ERR_NULL;
-        if (m.reserved != 0) return ADAFUSE_ERR_ARG;
-        if ((m.w_base == m.w_work) != (mats[0].w_base == mats[0].w_work)) return ADAFUSE_ERR_ARG;  // all in place or none
-        if (m.out < 1 || m.in < 8 || (m.in % 8) != 0 || m.ldw < m.in || (m.ldw % 8) != 0) return ADAFUSE_ERR_SHAPE;
-        // 32-bit offsets inside a tile (64 rows of ldw) and inside one expert's slice (rank x in, out x rank)
-        if (m.out > (1 << 22) || m.in > (1 << 22) || m.ldw > (1 << 24)) return ADAFUSE_ERR_SHAPE;
-        if (!aligned16(m.w_base) || !aligned16(m.w_work) || !aligned16(m.a_bank) || !aligned16(m.b_bank))
-            return ADAFUSE_ERR_ALIGN;
-    }
-    return ADAFUSE_OK;
 }
 
 // Tile shapes the matrix-core kernel is built for: rows, waves side by side, row groups in flight.
@@ -141,31 +121,30 @@ bool launch_mfma_any(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t
 
 // Which form of the rank-looped kernel runs (rank, term bucket): the unrolled kernel up to
 // 7 k-steps of 16 rank indices per tile, the overlapped one (W straight into LDS,
-// contraction meanwhile) from 8 on.  Measurement knob ADAFUSE_GEMM_FORM: 1 = the unrolled
+// contraction meanwhile) from 8 on.  ADAFUSE_OPT_GEMM_FORM forces one: 1 = the unrolled
 // form wherever it can take the launch, 3 = the overlapped form for short contractions too.
 enum GemmForm { kFormUnrolled, kFormOverlap };
 
 constexpr bool can_unroll(int r, int nt) { return nt <= 2 || (nt == 4 && r <= 16); }  // every row operand fits beside the W tile
 constexpr bool can_overlap(int r, int nt) { return nt * ((r + 15) / 16) <= 64; }
 
-GemmForm pick_gemm_form(int r, int nt)
+GemmForm pick_gemm_form(int r, int nt, int forced)
 {
-    static const int knob = [] { const char *e = std::getenv("ADAFUSE_GEMM_FORM"); return e ? std::atoi(e) : 0; }();
     const int steps = nt * ((r + 15) / 16);
     if (!can_unroll(r, nt)) return kFormOverlap;
     if (!can_overlap(r, nt)) return kFormUnrolled;
-    if (knob == 1) return kFormUnrolled;
-    if (knob == 3) return kFormOverlap;
+    if (forced == 1) return kFormUnrolled;
+    if (forced == 3) return kFormOverlap;
     return steps >= 8 ? kFormOverlap : kFormUnrolled;
 }
 
 template <int R, int NT, int NW>
-bool launch_gemm_form(const SwitchParams &p, int64_t n_tiles, hipStream_t s)
+bool launch_gemm_form(const SwitchParams &p, int forced_form, int64_t n_tiles, hipStream_t s)
 {
     static_assert(can_unroll(R, NT) || can_overlap(R, NT), "some form takes every (rank, terms)");
     const dim3 grid((unsigned)n_tiles), block(64 * NW);
     // a plain copy (no term: out-of-place UNMERGE) has nothing to overlap; W first, through registers, is the faster copy
-    switch (p.k == 0 && can_unroll(R, NT) ? kFormUnrolled : pick_gemm_form(R, NT)) {
+    switch (p.k == 0 && can_unroll(R, NT) ? kFormUnrolled : pick_gemm_form(R, NT, forced_form)) {
     case kFormOverlap:
         if constexpr (can_overlap(R, NT)) {
             hipLaunchKernelGGL((switch_gemm_overlap_kernel<R, NT, NW>), grid, block, 0, s, p);
@@ -183,33 +162,33 @@ bool launch_gemm_form(const SwitchParams &p, int64_t n_tiles, hipStream_t s)
 }
 
 template <int R, int NW>
-bool launch_gemm_rw(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t s)
+bool launch_gemm_rw(const SwitchParams &p, int nt, int form, int64_t n_tiles, hipStream_t s)
 {
     switch (nt) {
-    case 1: return launch_gemm_form<R, 1, NW>(p, n_tiles, s);
-    case 2: return launch_gemm_form<R, 2, NW>(p, n_tiles, s);
-    case 4: return launch_gemm_form<R, 4, NW>(p, n_tiles, s);
-    case 8: return launch_gemm_form<R, 8, NW>(p, n_tiles, s);
+    case 1: return launch_gemm_form<R, 1, NW>(p, form, n_tiles, s);
+    case 2: return launch_gemm_form<R, 2, NW>(p, form, n_tiles, s);
+    case 4: return launch_gemm_form<R, 4, NW>(p, form, n_tiles, s);
+    case 8: return launch_gemm_form<R, 8, NW>(p, form, n_tiles, s);
     default: return false;
     }
 }
 
 template <int R>
-bool launch_gemm_r(const SwitchParams &p, int nt, int waves, int64_t n_tiles, hipStream_t s)
+bool launch_gemm_r(const SwitchParams &p, int nt, int waves, int form, int64_t n_tiles, hipStream_t s)
 {
-    return waves == 8 ? launch_gemm_rw<R, 8>(p, nt, n_tiles, s) : launch_gemm_rw<R, 4>(p, nt, n_tiles, s);
+    return waves == 8 ? launch_gemm_rw<R, 8>(p, nt, form, n_tiles, s) : launch_gemm_rw<R, 4>(p, nt, form, n_tiles, s);
 }
 
-// nt = term bucket (1, 2, 4 or 8); waves = 4 or 8 per workgroup (tile 64 x 64 waves)
-bool launch_gemm(const SwitchParams &p, int nt, int waves, int64_t n_tiles, hipStream_t s)
+// nt = term bucket (1, 2, 4 or 8); waves = 4 or 8 per workgroup (tile 64 x 64 waves); form = forced form or 0
+bool launch_gemm(const SwitchParams &p, int nt, int waves, int form, int64_t n_tiles, hipStream_t s)
 {
     switch (p.r) {
-    case 4: return launch_gemm_r<4>(p, nt, waves, n_tiles, s);
-    case 8: return launch_gemm_r<8>(p, nt, waves, n_tiles, s);
-    case 16: return launch_gemm_r<16>(p, nt, waves, n_tiles, s);
-    case 32: return launch_gemm_r<32>(p, nt, waves, n_tiles, s);
-    case 64: return launch_gemm_r<64>(p, nt, waves, n_tiles, s);
-    case 128: return launch_gemm_r<128>(p, nt, waves, n_tiles, s);
+    case 4: return launch_gemm_r<4>(p, nt, waves, form, n_tiles, s);
+    case 8: return launch_gemm_r<8>(p, nt, waves, form, n_tiles, s);
+    case 16: return launch_gemm_r<16>(p, nt, waves, form, n_tiles, s);
+    case 32: return launch_gemm_r<32>(p, nt, waves, form, n_tiles, s);
+    case 64: return launch_gemm_r<64>(p, nt, waves, form, n_tiles, s);
+    case 128: return launch_gemm_r<128>(p, nt, waves, form, n_tiles, s);
     default: return false;
     }
 }
@@ -224,16 +203,15 @@ bool shape_fits(int shape, int r, int nt)
     });
 }
 
-// Tile shape for a context: a tuning override from the environment
-// (ADAFUSE_MFMA_SHAPE=<index>), else the default, else the first shape that fits.
-int pick_shape(int r, int n_terms)
+// Tile shape of the 4x4x4 kernel for a context: the one asked for (ADAFUSE_OPT_MFMA_SHAPE) if it
+// fits, else the default, else the first shape that fits.
+int pick_shape(int r, int n_terms, int asked)
 {
     const int nt = terms_bucket(n_terms);
     // measured on the Llama-shaped workloads: 64 x 512 tiles stream best; at inner
     // dimension 64 the per-tile operand fetch wants more rows per wave (256 x 512,
     // 8 row groups in flight)
-    int want = nt * r >= 64 ? 1 : 0;
-    if (const char *e = std::getenv("ADAFUSE_MFMA_SHAPE")) want = std::atoi(e);
+    const int want = asked >= 0 ? asked : (nt * r >= 64 ? 1 : 0);
     if (want >= 0 && want < kNumShapes && shape_fits(want, r, nt)) return want;
     for (int sh = 0; sh < kNumShapes; ++sh)
         if (shape_fits(sh, r, nt)) return sh;
@@ -241,7 +219,7 @@ int pick_shape(int r, int n_terms)
 }
 
 // The rank-looped kernel takes any rank that is a multiple of its MFMA depth (16), and 4 or 8 zero-padded to it.
-bool gemm_supported(int r) { return r == 4 || r == 8 || r == 16 || r == 32 || r == 64 || r == 128; }
+bool gemm_supported(int r) { return host::rank_supported(r); }
 
 // Kernel for AUTO, as measured on the Llama-shaped workloads: the rank-looped
 // 32x32x16 form is the fastest at every rank (80% of the HBM peak against 79% for
@@ -272,98 +250,43 @@ void free_tables(adafuse_ctx *c)
     c->d_tiles = nullptr;
 }
 
-// Column operands one XCD may cycle through per row block: half of its 4 MB L2 (the rest
-// holds row operands, the tables, and whatever of W passes through despite the streaming hints).
-constexpr size_t kPanelBytes = 2u << 20;
-
-// Workgroup i of a launch runs on XCD i % 8.  Reorder tiles [begin, end) so that
-// each XCD gets runs of G consecutive tiles instead of every eighth tile.
-void deal_to_xcds(std::vector<TileDev> &v, size_t begin, size_t end, size_t G)
+// Waves per workgroup of the rank-looped kernel when the caller leaves the choice to the library:
+// 8 (1 KB row pieces) where most of the weights sit at row pitches that are not a power of two
+// AND every launch of the context runs the unrolled form (the 8-wave overlapped form does not
+// fit three workgroups per CU); else 4 (512-byte pieces).  Measured on the Llama-2-13B shapes
+// (pitches 10240 and 27648 bytes): 8 waves +2.6 %; on the 7B shapes (8192 and 22016): -1.5 %.
+int auto_gemm_waves(const adafuse_ctx *c)
 {
-    const size_t n = end - begin;
-    if (n == 0 || G == 0) return;
-    std::vector<TileDev> sw;
-    sw.reserve(n);
-    std::vector<char> used(n, 0);
-    const size_t slots = ((n + 8 * G - 1) / (8 * G)) * 8 * G;
-    for (size_t i = 0; i < slots; ++i) {
-        const size_t x = i % 8, q = i / 8;
-        const size_t t = ((q / G) * 8 + x) * G + (q % G);
-        if (t < n) {
-            sw.push_back(v[begin + t]);
-            used[t] = 1;
-        }
-    }
-    for (size_t t = 0; t < n; ++t)
-        if (!used[t]) sw.push_back(v[begin + t]);
-    std::copy(sw.begin(), sw.end(), v.begin() + begin);
+    const int nt = terms_bucket(max_terms(c));
+    if (pick_gemm_form(c->r, nt, c->opt_form) != kFormUnrolled) return 4;
+    return host::odd_pitch_share(c->mats) > 0.75 ? 8 : 4;
 }
 
-// Tile order: matrix by matrix, row block by row block, column tiles innermost,
-// so workgroups that run together read neighbouring column strips of the same
-// rows (shared B slice) and the A/B slices of one matrix stay cache-resident
-// while that matrix streams through.
+// Builds the tables for `kernel` with the context's options and uploads them.
 adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
 {
     // everything is built aside and handed to the context at the end: a failure leaves it as it was
-    int tr = kValuTileRows, tc = kValuTileCols;
-    int mfma_shape = c->mfma_shape, gemm_waves = c->gemm_waves, order = c->order;
+    host::TablePlan plan;
+    plan.tile_rows = kValuTileRows;
+    plan.tile_cols = kValuTileCols;
+    int mfma_shape = c->mfma_shape, gemm_waves = c->gemm_waves;
     if (kernel == ADAFUSE_KERNEL_MFMA) {
-        mfma_shape = pick_shape(c->r, max_terms(c));
+        mfma_shape = pick_shape(c->r, max_terms(c), c->opt_mfma_shape);
         with_shape(mfma_shape, [&](auto sh) {
-            tr = decltype(sh)::TR;
-            tc = decltype(sh)::TC;
+            plan.tile_rows = decltype(sh)::TR;
+            plan.tile_cols = decltype(sh)::TC;
             return true;
         });
     } else if (kernel == ADAFUSE_KERNEL_GEMM) {
-        if (const char *e = std::getenv("ADAFUSE_GEMM_WAVES")) gemm_waves = std::atoi(e) == 8 ? 8 : 4;
-        tr = kGemmTileRows;
-        tc = kGemmWaveCols * gemm_waves;
+        gemm_waves = c->opt_waves == 4 || c->opt_waves == 8 ? c->opt_waves : auto_gemm_waves(c);
+        plan.tile_rows = kGemmTileRows;
+        plan.tile_cols = kGemmWaveCols * gemm_waves;
     }
-    // column tiles per panel: the panel's column operands (2 bytes x rank indices of a launch x columns) within kPanelBytes
-    const size_t kr = (size_t)max_terms(c) * c->r;
-    size_t panel_bytes = kPanelBytes;
-    if (const char *e = std::getenv("ADAFUSE_PANEL_KB")) panel_bytes = (size_t)std::max(1, std::atoi(e)) * 1024;
-    const int panel_tiles_max = (int)std::max<size_t>(1, panel_bytes / (2 * kr) / (size_t)tc);
-    std::vector<MatDev> hm(c->mats.size());
-    std::vector<TileDev> ht;
-    std::vector<int64_t> mat_off(1, 0);
-    int64_t elements = 0;
-    for (size_t i = 0; i < c->mats.size(); ++i) {
-        const adafuse_matrix_desc &m = c->mats[i];
-        hm[i] = MatDev{static_cast<const uint16_t *>(m.w_base), static_cast<uint16_t *>(m.w_work),
-                       static_cast<const uint16_t *>(m.a_bank), static_cast<const uint16_t *>(m.b_bank),
-                       m.out, m.in, m.ldw, 0};
-        const int nrt = (m.out + tr - 1) / tr, nct = (m.in + tc - 1) / tc;
-        // A wide matrix is walked in column panels: row block by row block inside a panel, so
-        // that the column-operand slices of one panel (selected experts x rank x panel columns)
-        // stay in an XCD's L2 while its row blocks stream by.  Without panels, rank 128 top-2 on
-        // an 11008-wide matrix cycles 5.6 MB of column operands through a 4 MB L2 once per row
-        // block (measured: 1.30 x the algorithmic HBM traffic for the whole model).
-        const int n_panels = (nct + panel_tiles_max - 1) / panel_tiles_max;
-        const int panel_tiles = (nct + n_panels - 1) / n_panels;
-        for (int ct0 = 0; ct0 < nct; ct0 += panel_tiles)
-            for (int rt = 0; rt < nrt; ++rt)
-                for (int ct = ct0; ct < std::min(nct, ct0 + panel_tiles); ++ct) {
-                    const int row0 = rt * tr, col0 = ct * tc;
-                    const size_t off = (size_t)row0 * m.ldw + col0;
-                    ht.push_back(TileDev{hm[i].w_base + off, hm[i].w_work + off, (uint32_t)i, row0, col0, m.ldw,
-                                         m.out - row0, m.in - col0});
-                }
-        elements += (int64_t)m.out * m.in;
-        mat_off.push_back((int64_t)ht.size());
-    }
-    if (ht.size() > 0x3fffffffu) return ADAFUSE_ERR_SHAPE;
-    if (const char *e = std::getenv("ADAFUSE_ORDER")) order = std::atoi(e);
-    // second section: the same tiles grouped per matrix, for the one-launch-per-matrix form
-    const size_t n = ht.size();
-    ht.insert(ht.end(), ht.begin(), ht.begin() + n);
-    if (order >= 1) {
-        auto run = [&](size_t count) { return order == 1 ? (count + 7) / 8 : (size_t)order; };
-        deal_to_xcds(ht, 0, n, run(n));
-        for (size_t i = 0; i + 1 < mat_off.size(); ++i)
-            deal_to_xcds(ht, n + mat_off[i], n + mat_off[i + 1], run((size_t)(mat_off[i + 1] - mat_off[i])));
-    }
+    plan.inner = (size_t)max_terms(c) * c->r;
+    plan.panel_bytes = (size_t)std::max(1, c->opt_panel_kb) * 1024;
+    plan.xcd_run = c->opt_xcd_run;
+    host::Tables t;
+    if (!host::build_tile_tables(c->mats, plan, t)) return ADAFUSE_ERR_SHAPE;
 
     int device = -1;
     if (hipGetDevice(&device) != hipSuccess) return ADAFUSE_ERR_HIP;
@@ -371,13 +294,13 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
     if (hipGetSymbolAddress(&scratch_ptr, HIP_SYMBOL(scratch)) != hipSuccess || !scratch_ptr) return ADAFUSE_ERR_HIP;
     MatDev *dm = nullptr;
     TileDev *dt = nullptr;
-    if (hipMalloc(&dm, hm.size() * sizeof(MatDev)) != hipSuccess) return ADAFUSE_ERR_HIP;
-    if (hipMalloc(&dt, ht.size() * sizeof(TileDev)) != hipSuccess) {
+    if (hipMalloc(&dm, t.mats.size() * sizeof(MatDev)) != hipSuccess) return ADAFUSE_ERR_HIP;
+    if (hipMalloc(&dt, t.tiles.size() * sizeof(TileDev)) != hipSuccess) {
         (void)hipFree(dm);
         return ADAFUSE_ERR_HIP;
     }
-    if (hipMemcpy(dm, hm.data(), hm.size() * sizeof(MatDev), hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(dt, ht.data(), ht.size() * sizeof(TileDev), hipMemcpyHostToDevice) != hipSuccess) {
+    if (hipMemcpy(dm, t.mats.data(), t.mats.size() * sizeof(MatDev), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(dt, t.tiles.data(), t.tiles.size() * sizeof(TileDev), hipMemcpyHostToDevice) != hipSuccess) {
         (void)hipFree(dm);
         (void)hipFree(dt);
         return ADAFUSE_ERR_HIP;
@@ -390,12 +313,11 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
     c->kernel = kernel;
     c->mfma_shape = mfma_shape;
     c->gemm_waves = gemm_waves;
-    c->order = order;
-    c->tile_rows = tr;
-    c->tile_cols = tc;
-    c->n_tiles = (int64_t)n;
-    c->mat_tile_off.swap(mat_off);
-    c->elements = elements;
+    c->tile_rows = plan.tile_rows;
+    c->tile_cols = plan.tile_cols;
+    c->n_tiles = t.n_tiles;
+    c->mat_tile_off.swap(t.mat_off);
+    c->elements = t.elements;
     return ADAFUSE_OK;
 }
 
@@ -408,9 +330,8 @@ adafuse_status adafuse_create(const adafuse_matrix_desc *mats, int32_t n_mats, i
 {
     if (!ctx) return ADAFUSE_ERR_NULL;
     *ctx = nullptr;
-    adafuse_status st = validate_mats(mats, n_mats, E, r, k_max);
+    adafuse_status st = host::validate_mats(mats, n_mats, E, r, k_max);
     if (st != ADAFUSE_OK) return st;
-    if (mats[0].w_base == mats[0].w_work && 2 * k_max > kMaxTerms) return ADAFUSE_ERR_ARG;  // an in-place SWAP carries 2k terms
     adafuse_ctx *c = new (std::nothrow) adafuse_ctx();
     if (!c) return ADAFUSE_ERR_HIP;
     try {  // the host tables are std::vectors: no exception may cross the C boundary
@@ -440,22 +361,66 @@ adafuse_status adafuse_destroy(adafuse_ctx *ctx)
     return ADAFUSE_OK;
 }
 
-adafuse_status adafuse_set_kernel(adafuse_ctx *ctx, int32_t kernel)
+adafuse_status adafuse_set_option(adafuse_ctx *ctx, int32_t option, int32_t value)
 {
     if (!ctx) return ADAFUSE_ERR_NULL;
-    if (kernel == ADAFUSE_KERNEL_AUTO) kernel = auto_kernel(ctx->r, max_terms(ctx));
-    if (kernel != ADAFUSE_KERNEL_VALU && kernel != ADAFUSE_KERNEL_MFMA && kernel != ADAFUSE_KERNEL_GEMM)
-        return ADAFUSE_ERR_ARG;
-    if (kernel == ADAFUSE_KERNEL_MFMA && !mfma_supported(ctx->r, max_terms(ctx))) return ADAFUSE_ERR_ARG;
-    if (kernel == ADAFUSE_KERNEL_GEMM && !gemm_supported(ctx->r)) return ADAFUSE_ERR_ARG;
-    if (kernel == ctx->kernel) return ADAFUSE_OK;
-    if (!on_ctx_device(ctx)) return ADAFUSE_ERR_ARG;
-    if (hipDeviceSynchronize() != hipSuccess) return ADAFUSE_ERR_HIP;  // no launch may still read the old table
-    try {
-        return build_tables(ctx, kernel);  // on failure the context keeps its old tables and kernel
-    } catch (...) {
-        return ADAFUSE_ERR_HIP;
+    int32_t kernel = ctx->kernel;
+    adafuse_ctx saved_opts;  // only the option fields are used
+    saved_opts.opt_waves = ctx->opt_waves;
+    saved_opts.opt_form = ctx->opt_form;
+    saved_opts.opt_xcd_run = ctx->opt_xcd_run;
+    saved_opts.opt_panel_kb = ctx->opt_panel_kb;
+    saved_opts.opt_mfma_shape = ctx->opt_mfma_shape;
+    switch (option) {
+    case ADAFUSE_OPT_KERNEL:
+        kernel = value == ADAFUSE_KERNEL_AUTO ? auto_kernel(ctx->r, max_terms(ctx)) : value;
+        if (kernel != ADAFUSE_KERNEL_VALU && kernel != ADAFUSE_KERNEL_MFMA && kernel != ADAFUSE_KERNEL_GEMM)
+            return ADAFUSE_ERR_ARG;
+        if (kernel == ADAFUSE_KERNEL_MFMA && !mfma_supported(ctx->r, max_terms(ctx))) return ADAFUSE_ERR_ARG;
+        if (kernel == ADAFUSE_KERNEL_GEMM && !gemm_supported(ctx->r)) return ADAFUSE_ERR_ARG;
+        if (kernel == ctx->kernel) return ADAFUSE_OK;
+        break;
+    case ADAFUSE_OPT_GEMM_WAVES:
+        if (value != 0 && value != 4 && value != 8) return ADAFUSE_ERR_ARG;
+        ctx->opt_waves = value;
+        break;
+    case ADAFUSE_OPT_GEMM_FORM:
+        if (value != 0 && value != 1 && value != 3) return ADAFUSE_ERR_ARG;
+        ctx->opt_form = value;
+        break;
+    case ADAFUSE_OPT_XCD_RUN:
+        if (value < 0) return ADAFUSE_ERR_ARG;
+        ctx->opt_xcd_run = value;
+        break;
+    case ADAFUSE_OPT_PANEL_KB:
+        if (value < 1) return ADAFUSE_ERR_ARG;
+        ctx->opt_panel_kb = value;
+        break;
+    case ADAFUSE_OPT_MFMA_SHAPE:
+        if (value < -1 || value >= kNumShapes) return ADAFUSE_ERR_ARG;
+        ctx->opt_mfma_shape = value;
+        break;
+    default: return ADAFUSE_ERR_ARG;
     }
+    adafuse_status st = ADAFUSE_ERR_ARG;
+    if (on_ctx_device(ctx)) {
+        st = ADAFUSE_ERR_HIP;
+        if (hipDeviceSynchronize() == hipSuccess) {  // no launch may still read the old table
+            try {
+                st = build_tables(ctx, kernel);
+            } catch (...) {
+                st = ADAFUSE_ERR_HIP;
+            }
+        }
+    }
+    if (st != ADAFUSE_OK) {  // the context keeps the kernel, tables and options it had
+        ctx->opt_waves = saved_opts.opt_waves;
+        ctx->opt_form = saved_opts.opt_form;
+        ctx->opt_xcd_run = saved_opts.opt_xcd_run;
+        ctx->opt_panel_kb = saved_opts.opt_panel_kb;
+        ctx->opt_mfma_shape = saved_opts.opt_mfma_shape;
+    }
+    return st;
 }
 
 adafuse_status adafuse_get_info(const adafuse_ctx *ctx, adafuse_info *info)
@@ -531,7 +496,7 @@ adafuse_status switch_launches(adafuse_ctx *ctx, const int32_t *idx_prev, const 
             if (!launched) return ADAFUSE_ERR_ARG;
         } else if (ctx->kernel == ADAFUSE_KERNEL_GEMM) {
             // the copy (nothing selected) runs through the one-term instance
-            if (!launch_gemm(p, terms_bucket(n_terms > 0 ? n_terms : 1), ctx->gemm_waves, count, s)) return ADAFUSE_ERR_ARG;
+            if (!launch_gemm(p, terms_bucket(n_terms > 0 ? n_terms : 1), ctx->gemm_waves, ctx->opt_form, count, s)) return ADAFUSE_ERR_ARG;
         } else {
             hipLaunchKernelGGL(switch_valu_kernel, dim3((unsigned)count), dim3(256), valu_lds, s, p);
         }
@@ -644,7 +609,7 @@ const char *adafuse_switch_kernel_name(const adafuse_ctx *ctx, int32_t k, int32_
     case ADAFUSE_KERNEL_MFMA: return copy_only ? "switch_copy_kernel" : "switch_mfma_kernel";
     case ADAFUSE_KERNEL_GEMM:
         if (copy_only) return "switch_gemm_kernel";
-        return pick_gemm_form(ctx->r, terms_bucket(n_terms)) == kFormOverlap ? "switch_gemm_overlap_kernel" : "switch_gemm_kernel";
+        return pick_gemm_form(ctx->r, terms_bucket(n_terms), ctx->opt_form) == kFormOverlap ? "switch_gemm_overlap_kernel" : "switch_gemm_kernel";
     default: return "switch_valu_kernel";
     }
 }

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "table_types.hpp"
+
 namespace adafuse {
 
 typedef __attribute__((ext_vector_type(4))) short short4_t;
@@ -12,32 +14,6 @@ typedef __attribute__((ext_vector_type(2))) float float2_t;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int uint4_t;
 typedef __attribute__((ext_vector_type(2))) unsigned int uint2_t;
-
-constexpr int kMaxTerms = 8;  // experts accumulated per element in one pass
-
-// One adapted matrix: the device copy of a caller descriptor (section "SGMM
-// Kernel": pointer arrays plus the shape of each segment).
-struct MatDev {
-    const uint16_t *w_base;
-    uint16_t *w_work;
-    const uint16_t *a_bank;  // [E][r][in]
-    const uint16_t *b_bank;  // [E][out][r]
-    int32_t out, in, ldw, pad;
-};
-
-// One workgroup's share of the batched update.  The entry carries everything the
-// W loads need (tile origin in both buffers, leading dimension, bounds), so they
-// can be issued after ONE table read; the matrix table is read alongside, for
-// the operand banks only.
-struct TileDev {
-    const uint16_t *w_src;  // &W_base[row0][col0]
-    uint16_t *w_dst;        // &W_work[row0][col0]
-    uint32_t mat;
-    int32_t row0, col0;
-    int32_t ldw;
-    int32_t rows_left;      // out - row0
-    int32_t cols_left;      // in - col0
-};
 
 struct SwitchParams {
     const MatDev *mats;

@@ -13,9 +13,6 @@
 
 namespace adafuse {
 
-constexpr int kMaxExperts = 64;
-constexpr int kMaxTopK = 8;
-
 struct PregateParams {
     const uint16_t *hidden;    // [T][d]
     const uint16_t *w_router;  // [E][d]

@@ -111,5 +111,5 @@ def test_switch_and_misc_reject_null_context(L):
     assert L.adafuse_switch_per_matrix(None, None, None, None, None, 2, 2.0, 0, None) == ERR_NULL
     assert L.adafuse_forward_merged(None, None, None, None) == ERR_NULL
     assert L.adafuse_forward_dynamic(None, None, None, 2, 2.0, None, None, None, None) == ERR_NULL
-    assert L.adafuse_set_kernel(None, 1) == ERR_NULL
+    assert L.adafuse_set_option(None, 0, 1) == ERR_NULL
     assert L.adafuse_get_info(None, None) == ERR_NULL
