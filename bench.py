@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--graph", action="store_true",
                     help="capture the whole token sequence (T x [pregate, switch]) in one HIP graph and replay it; "
                          "for launch-bound workloads (toy).  Reported separately as graph_us_per_token")
+    ap.add_argument("--prefill", type=int, default=0, metavar="T",
+                    help="instead of the switch: time adafuse_prefill for T tokens through every matrix of the "
+                         "workload (un-merged adapters, per-token decisions) and print that as the JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-copy-ceiling", action="store_true",
                     help="skip the plain-copy launches after the timed loop (for counter runs that average over dispatches)")
@@ -121,6 +124,44 @@ def forward_context(torch, af, ctx, wl, mats, idx, gates, stream, reps=20):
     return res
 
 
+def prefill_bench(torch, af, ctx, wl, mats, hidden, router, T, stream, reps):
+    """T tokens through every matrix (one adafuse_prefill call per matrix: two launches each)."""
+    dev = mats[0][0].device
+    reps_h = (T + wl.T - 1) // wl.T
+    h = hidden.repeat(reps_h, 1)[:T].contiguous()
+    idx, gates, _ = af.pregate(h, router, wl.k, stream=stream)
+    xs = {i: torch.randn((T, i), device=dev).to(torch.bfloat16) for i in {m[0].shape[1] for m in mats}}
+    ys = {o: torch.empty((T, o), dtype=torch.float32, device=dev) for o in {m[0].shape[0] for m in mats}}
+    ws = torch.empty(4 * T * wl.k * max(wl.r, 8), dtype=torch.uint8, device=dev)
+
+    def run():
+        for mi, m in enumerate(mats):
+            ctx.prefill(mi, xs[m[0].shape[1]], idx, gates, wl.scale, y=ys[m[0].shape[0]], workspace=ws, stream=stream)
+
+    with torch.cuda.stream(stream):
+        t = timed_launches(torch, stream, run, reps, warm=2)
+    w_bytes = 2 * wl.elements
+    io_bytes = sum(2 * T * m[0].shape[1] + 4 * T * m[0].shape[0] for m in mats)
+    flops = 2 * T * wl.elements + 2 * T * wl.k * wl.r * sum(m[0].shape[0] + m[0].shape[1] for m in mats)
+    sec = t["mean"] * 1e-6
+    hbm = (w_bytes + io_bytes) / sec / 1e9
+    tf = flops / sec / 1e12
+    bound = "hbm" if T * 2 < 2 * MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS else "mfma"   # flops per W byte = T
+    return {
+        "metric": "prefill latency, all adapted matrices, un-merged adapters with per-token decisions (us)",
+        "value": t["mean"], "unit": "us", "n_gpus": 1, "steps": reps, "warmup": 2, "ms_per_step": t["mean"] * 1e-3,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "tokens": T, "matrices": wl.n_mats, "E": wl.E, "r": wl.r, "k": wl.k,
+                   "launches": 2 * wl.n_mats, "step": "adafuse_prefill on every matrix, one stream"},
+        "roofline": {"bound": bound,
+                     "achieved": hbm if bound == "hbm" else tf, "peak": HBM_PEAK_GBS if bound == "hbm" else MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
+                     "frac": hbm / HBM_PEAK_GBS if bound == "hbm" else tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "prefill_up_kernel (+ prefill_down_kernel)", "hbm_GBs": hbm, "mfma_TFLOPs": tf,
+                     "algorithmic_bytes": w_bytes + io_bytes, "algorithmic_flops": flops, "median_us": t["median"]},
+    }
+
+
 def timed_launches(torch, stream, fn, reps, warm=3):
     """Mean and median us of one enqueue of fn on stream, from an event pair around each."""
     for _ in range(warm):
@@ -163,6 +204,12 @@ def main():
     ctx.set_kernel({"auto": af.KERNEL_AUTO, "valu": af.KERNEL_VALU, "mfma": af.KERNEL_MFMA, "gemm": af.KERNEL_GEMM}[args.kernel])
     info = ctx.info()
     kernel_name = {af.KERNEL_VALU: "valu", af.KERNEL_MFMA: "mfma", af.KERNEL_GEMM: "gemm"}[info.kernel]
+
+    if args.prefill > 0:
+        out = prefill_bench(torch, af, ctx, wl, mats, hidden, router, args.prefill, torch.cuda.Stream(device=dev), max(2, min(args.steps, 20)))
+        ctx.close()
+        print(json.dumps(out))
+        return
 
     T = wl.T
     idx = torch.empty((T, wl.k), dtype=torch.int32, device=dev)

@@ -36,6 +36,7 @@
 #ifndef ADAFUSE_H
 #define ADAFUSE_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -255,6 +256,36 @@ adafuse_status adafuse_switch_per_matrix(adafuse_ctx *ctx,
 adafuse_status adafuse_forward_merged(adafuse_ctx *ctx, const void *x, float *y, void *hip_stream);
 adafuse_status adafuse_forward_dynamic(adafuse_ctx *ctx, const int32_t *idx, const float *gates, int32_t k,
                                        float scale, const void *x, float *y, float *z, void *hip_stream);
+
+/*
+ * Prefill: T tokens through ONE adapted matrix of the context, every token with its own
+ * routing decision (section "Decoding Phase": in the prefill phase the tokens of a prompt
+ * select different experts, so no single merged weight serves them and the adapters are
+ * applied un-merged, Eq.2 with the pre-gated G^1(x^1) of each token):
+ *   y[t] = W_base x[t] + scale * sum_{j<k} gates[t][j] * B_{idx[t][j]} (A_{idx[t][j]} x[t]),   t < T.
+ * mat      index of the matrix in the array given to adafuse_create (0 <= mat < n_mats)
+ * x        DEVICE bf16 [T][in], contiguous, 16-byte aligned
+ * idx      DEVICE int32 [T][k], gates DEVICE fp32 [T][k]: what adafuse_pregate wrote for these
+ *          tokens; 1 <= k <= k_max.  Indices outside [0,E) are clamped.  An expert listed
+ *          twice for a token counts twice (its gates add).
+ * y        DEVICE fp32 [T][out], contiguous, 16-byte aligned; every element is written once
+ *          (no accumulation into previous contents, no atomics: the same bits on every run)
+ * workspace  DEVICE, 16-byte aligned, at least 4 * T * k * max(r, 8) bytes (workspace_bytes is
+ *          checked): the scaled down-projections s g A x of every (token, selection) as two
+ *          bf16 planes (value and rounding remainder, 16 significant bits).  Owned by the
+ *          caller; its previous contents do not matter and nothing in it needs clearing.
+ * Arithmetic: bf16 operands on the matrix cores, fp32 accumulation; the inner dimension of
+ * each output element is summed in four fixed parts that are added in a fixed order.
+ * Two launches on `hip_stream` (down projection; base product with the up projection as
+ * further inner dimension), no allocation, no synchronisation.  Needs an out-of-place
+ * context (the base weights must be unmodified).
+ * Errors: NULL pointer -> ERR_NULL; mat, T < 0, k out of range, in-place context, workspace
+ * too small, wrong device -> ERR_ARG; misaligned x / y / workspace -> ERR_ALIGN;
+ * T * in or T * k * r beyond 2^30 elements -> ERR_SHAPE.  T == 0 is a no-op.
+ */
+adafuse_status adafuse_prefill(adafuse_ctx *ctx, int32_t mat, const void *x, int32_t T,
+                               const int32_t *idx, const float *gates, int32_t k, float scale,
+                               float *y, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * adafuse_forward_dynamic for callers that cannot allocate device memory or hand over a

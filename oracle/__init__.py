@@ -188,6 +188,25 @@ def dynamic_adapter_forward(w_base, a_bank, b_bank, idx, gates, scale, x):
     return y
 
 
+def prefill(w_base, a_bank, b_bank, idx, gates, scale, x_bits, tokens=None):
+    """Prefill of one adapted matrix (section "Decoding Phase": many tokens, each with its own
+    pre-gated decision, adapters un-merged): row t of the result is Eq.2 for token t,
+        y[t] = W_base x[t] + s * sum_j gates[t][j] * B_{idx[t][j]} (A_{idx[t][j]} x[t]),
+    taken token by token with dynamic_adapter_forward.  x_bits [T][in] bf16 bit patterns,
+    idx [T][k], gates [T][k] fp32.  tokens = the rows wanted (default: all); returns fp64
+    [len(tokens)][out].
+    """
+    xb = _arr(x_bits, np.uint16)
+    i2 = _arr(idx, np.int32)
+    g2 = _arr(gates, np.float32)
+    if xb.ndim != 2 or i2.ndim != 2 or i2.shape != g2.shape or i2.shape[0] != xb.shape[0]:
+        raise ValueError("oracle.prefill: x [T][in], idx [T][k], gates [T][k] expected")
+    rows = range(xb.shape[0]) if tokens is None else list(tokens)
+    xs = bf16_to_f64(xb)
+    return np.stack([dynamic_adapter_forward(w_base, a_bank, b_bank, i2[t], g2[t], scale, xs[t]) for t in rows]) \
+        if len(rows) else np.empty((0, _arr(w_base, np.uint16).shape[0]), np.float64)
+
+
 def gemv_bf16(w, x):
     """y = W x with W bf16 bits and x fp64 (Eq.3 on a merged matrix)."""
     wv = _arr(w, np.uint16)

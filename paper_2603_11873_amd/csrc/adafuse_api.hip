@@ -11,6 +11,7 @@
 #include "device_types.hpp"
 #include "host_tables.hpp"
 #include "forward.hpp"
+#include "prefill.hpp"
 #include "pregate.hpp"
 #include "switch_gemm.hpp"
 #include "switch_gemm_overlap.hpp"
@@ -594,6 +595,47 @@ adafuse_status adafuse_forward_dynamic_static(adafuse_ctx *ctx, const int32_t *i
     // every entry of z that a launch reads was written by the launch before it on the same stream:
     // nothing of the previous call's contents is used, nothing has to be cleared
     return forward_dynamic_launches(ctx, idx_host, gates_host, k, scale, x, y, ctx->scratch, hip_stream);
+}
+
+adafuse_status adafuse_prefill(adafuse_ctx *ctx, int32_t mat, const void *x, int32_t T, const int32_t *idx,
+                               const float *gates, int32_t k, float scale, float *y, void *workspace,
+                               size_t workspace_bytes, void *hip_stream)
+{
+    if (!ctx) return ADAFUSE_ERR_NULL;
+    if (mat < 0 || mat >= (int32_t)ctx->mats.size() || T < 0 || k < 1 || k > ctx->k_max) return ADAFUSE_ERR_ARG;
+    if (ctx->inplace) return ADAFUSE_ERR_ARG;  // needs the unmodified base weights
+    if (T == 0) return ADAFUSE_OK;             // no tokens: nothing to read or write
+    if (!x || !idx || !gates || !y || !workspace) return ADAFUSE_ERR_NULL;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(workspace)) return ADAFUSE_ERR_ALIGN;
+    const adafuse_matrix_desc &m = ctx->mats[(size_t)mat];
+    const int rp = ctx->r < 8 ? 8 : ctx->r;  // a slot holds whole 16-byte pieces
+    const uint64_t plane = (uint64_t)T * (uint64_t)k * (uint64_t)rp * 2u;
+    if (workspace_bytes < 2 * plane) return ADAFUSE_ERR_ARG;
+    // the kernels address X and the workspace planes through 32-bit descriptors and offsets
+    if ((uint64_t)T * (uint64_t)m.in * 2u >= (1ull << 31) || plane >= (1ull << 31)) return ADAFUSE_ERR_SHAPE;
+    if (!on_ctx_device(ctx)) return ADAFUSE_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    PrefillParams p{static_cast<const uint16_t *>(m.w_base), static_cast<const uint16_t *>(m.a_bank),
+                    static_cast<const uint16_t *>(m.b_bank), static_cast<const uint16_t *>(x), idx, gates, y,
+                    static_cast<uint16_t *>(workspace), static_cast<uint16_t *>(workspace) + plane / 2,
+                    m.out, m.in, m.ldw, T, ctx->E, ctx->r, rp, k, scale};
+    const dim3 down_grid((unsigned)((T + 31) / 32), (unsigned)ctx->E);
+    if (ctx->r <= 32)
+        hipLaunchKernelGGL(prefill_down_kernel<1>, down_grid, dim3(256), 0, s, p);
+    else if (ctx->r == 64)
+        hipLaunchKernelGGL(prefill_down_kernel<2>, down_grid, dim3(256), 0, s, p);
+    else
+        hipLaunchKernelGGL(prefill_down_kernel<4>, down_grid, dim3(256), 0, s, p);
+    // 128 tokens per workgroup once that still fills the chip several times over, else 64
+    const int strips = (m.out + 31) / 32;
+    const bool big = (int64_t)((T + 127) / 128) * strips >= 1024;
+    const int m_tiles = big ? (T + 127) / 128 : (T + 63) / 64;
+    const unsigned up_grid = (unsigned)(((strips + 7) / 8) * 8 * m_tiles);
+    if (big)
+        hipLaunchKernelGGL(prefill_up_kernel<4>, dim3(up_grid), dim3(256), 0, s, p, m_tiles, strips);
+    else
+        hipLaunchKernelGGL(prefill_up_kernel<2>, dim3(up_grid), dim3(256), 0, s, p, m_tiles, strips);
+    return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
 }
 
 const char *adafuse_switch_kernel_name(const adafuse_ctx *ctx, int32_t k, int32_t mode)

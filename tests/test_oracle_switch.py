@@ -106,6 +106,34 @@ def test_merged_gemv_equals_dynamic_adapter_output(oracle):
     assert np.max(np.abs(y_m - y_dyn)) > 0
 
 
+def test_prefill_is_the_per_token_merged_backbone(oracle):
+    # Many tokens, each with its own decision: row t must equal the mat-vec of the weights merged
+    # with token t's experts (Eq.2 <=> Eq.3 token by token), and a library statement of the sum.
+    w, a, b = _rand_case(40, 56, 6, 4, 11, bstd=0.2)
+    rng = np.random.default_rng(3)
+    T, k = 9, 2
+    x = (rng.standard_normal((T, 56))).astype(np.float32)
+    xb = oracle.f64_to_bf16(x.astype(np.float64))
+    xs = _f64(xb)
+    idx = np.array([rng.permutation(6)[:k] for _ in range(T)], np.int32)
+    gates = rng.random((T, k)).astype(np.float32)
+    y = oracle.prefill(w, a, b, idx, gates, 2.0, xb)
+    assert y.shape == (T, 40)
+    for t in range(T):
+        merged = oracle.merge(w, a, b, idx[t], gates[t], 2.0, rounded=False)
+        assert np.allclose(y[t], merged @ xs[t], rtol=1e-12, atol=1e-14)
+        ref = _f64(w) @ xs[t] + 2.0 * sum(float(g) * (_f64(b[e]) @ (_f64(a[e]) @ xs[t])) for e, g in zip(idx[t], gates[t]))
+        assert np.allclose(y[t], ref, rtol=1e-12, atol=1e-14)
+        # pairing a token with its neighbour's decision is a different result
+        other = oracle.merge(w, a, b, idx[(t + 1) % T], gates[(t + 1) % T], 2.0, rounded=False)
+        assert not np.allclose(y[t], other @ xs[t], rtol=1e-6, atol=1e-9)
+    # a subset of rows, and an expert listed twice counts twice
+    assert np.array_equal(oracle.prefill(w, a, b, idx, gates, 2.0, xb, tokens=[7, 2]), y[[7, 2]])
+    twice = oracle.prefill(w, a, b, [[3, 3]], [[0.25, 0.5]], 2.0, xb[:1])
+    once = oracle.prefill(w, a, b, [[3]], [[0.75]], 2.0, xb[:1])
+    assert np.allclose(twice, once, rtol=1e-13, atol=1e-15)
+
+
 def test_permutation_of_selection_is_irrelevant(oracle):
     w, a, b = _rand_case(16, 32, 8, 4, 6, bstd=0.2)
     idx, gates = [5, 2, 7], [0.2, 0.5, 0.3]
