@@ -31,6 +31,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="llama2_7b_all")
     ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma", "gemm"])
+    ap.add_argument("--gemm-form", type=int, default=0, choices=[0, 1, 3, 4],
+                    help="ADAFUSE_OPT_GEMM_FORM: 0 library's choice, 1 unrolled, 3 overlapped (64-row tiles), 4 128-row tiles")
+    ap.add_argument("--gemm-waves", type=int, default=0, choices=[0, 4, 8], help="ADAFUSE_OPT_GEMM_WAVES (0: library's choice)")
     ap.add_argument("--mode", default="swap", choices=["swap", "unmerge"],
                     help="unmerge times the plain W_base->W_work copy over the same tile table")
     ap.add_argument("--inplace", action="store_true",
@@ -202,6 +205,10 @@ def main():
     router = wlmod.gen_router(wl, "cuda")
     ctx = af.Context(mats, wl.k)
     ctx.set_kernel({"auto": af.KERNEL_AUTO, "valu": af.KERNEL_VALU, "mfma": af.KERNEL_MFMA, "gemm": af.KERNEL_GEMM}[args.kernel])
+    if args.gemm_form:
+        ctx.set_option(af.OPT_GEMM_FORM, args.gemm_form)
+    if args.gemm_waves:
+        ctx.set_option(af.OPT_GEMM_WAVES, args.gemm_waves)
     info = ctx.info()
     kernel_name = {af.KERNEL_VALU: "valu", af.KERNEL_MFMA: "mfma", af.KERNEL_GEMM: "gemm"}[info.kernel]
 

@@ -15,6 +15,7 @@
 #include "pregate.hpp"
 #include "switch_gemm.hpp"
 #include "switch_gemm_overlap.hpp"
+#include "switch_gemm_tall.hpp"
 #include "switch_mfma.hpp"
 #include "switch_valu.hpp"
 
@@ -43,6 +44,8 @@ struct adafuse_ctx {
     float *scratch = nullptr;            // this device's copy of the file-scope scratch array
     MatDev *d_mats = nullptr;
     TileDev *d_tiles = nullptr;          // [0, n_tiles): whole model; [n_tiles, 2 n_tiles): matrix by matrix
+    TileDev *d_tall = nullptr;           // the whole model in tiles of 128 rows (the tall form of the rank-looped kernel), or null
+    int64_t n_tall = 0;
     std::vector<int64_t> mat_tile_off;   // per-matrix ranges inside the second section (n_mats + 1 entries)
 };
 
@@ -124,14 +127,20 @@ bool launch_mfma_any(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t
 // 7 k-steps of 16 rank indices per tile, the overlapped one (W straight into LDS,
 // contraction meanwhile) from 8 on.  ADAFUSE_OPT_GEMM_FORM forces one: 1 = the unrolled
 // form wherever it can take the launch, 3 = the overlapped form for short contractions too.
-enum GemmForm { kFormUnrolled, kFormOverlap };
+enum GemmForm { kFormUnrolled, kFormOverlap, kFormTall };
 
 constexpr bool can_unroll(int r, int nt) { return nt <= 2 || (nt == 4 && r <= 16); }  // every row operand fits beside the W tile
 constexpr bool can_overlap(int r, int nt) { return nt * ((r + 15) / 16) <= 64; }
+constexpr bool can_tall(int r, int nt) { return nt * ((r + 15) / 16) == 8 || nt * ((r + 15) / 16) == 16; }
 
-GemmForm pick_gemm_form(int r, int nt, int forced)
+// forced: ADAFUSE_OPT_GEMM_FORM (0 = by the length of the contraction); tall_ok: the context holds the
+// table of 128-row tiles (4-wave workgroups, whole-model launch).  The 128-row form is only run on
+// request: it halves the column-operand bytes per W byte, but with two workgroups per CU instead of
+// three it measured no faster (rank 128 top-2: 6390 against 6290 us; rank 64: 4800 against 4510 us).
+GemmForm pick_gemm_form(int r, int nt, int forced, bool tall_ok)
 {
     const int steps = nt * ((r + 15) / 16);
+    if (forced == 4 && tall_ok && can_tall(r, nt)) return kFormTall;
     if (!can_unroll(r, nt)) return kFormOverlap;
     if (!can_overlap(r, nt)) return kFormUnrolled;
     if (forced == 1) return kFormUnrolled;
@@ -140,12 +149,17 @@ GemmForm pick_gemm_form(int r, int nt, int forced)
 }
 
 template <int R, int NT, int NW>
-bool launch_gemm_form(const SwitchParams &p, int forced_form, int64_t n_tiles, hipStream_t s)
+bool launch_gemm_form(const SwitchParams &p, GemmForm form, int64_t n_tiles, hipStream_t s)
 {
     static_assert(can_unroll(R, NT) || can_overlap(R, NT), "some form takes every (rank, terms)");
     const dim3 grid((unsigned)n_tiles), block(64 * NW);
-    // a plain copy (no term: out-of-place UNMERGE) has nothing to overlap; W first, through registers, is the faster copy
-    switch (p.k == 0 && can_unroll(R, NT) ? kFormUnrolled : pick_gemm_form(R, NT, forced_form)) {
+    switch (form) {
+    case kFormTall:
+        if constexpr (can_tall(R, NT) && NW == 4) {
+            hipLaunchKernelGGL((switch_gemm_tall_kernel<R, NT>), grid, block, 0, s, p);
+            return true;
+        }
+        break;
     case kFormOverlap:
         if constexpr (can_overlap(R, NT)) {
             hipLaunchKernelGGL((switch_gemm_overlap_kernel<R, NT, NW>), grid, block, 0, s, p);
@@ -163,7 +177,7 @@ bool launch_gemm_form(const SwitchParams &p, int forced_form, int64_t n_tiles, h
 }
 
 template <int R, int NW>
-bool launch_gemm_rw(const SwitchParams &p, int nt, int form, int64_t n_tiles, hipStream_t s)
+bool launch_gemm_rw(const SwitchParams &p, int nt, GemmForm form, int64_t n_tiles, hipStream_t s)
 {
     switch (nt) {
     case 1: return launch_gemm_form<R, 1, NW>(p, form, n_tiles, s);
@@ -175,13 +189,13 @@ bool launch_gemm_rw(const SwitchParams &p, int nt, int form, int64_t n_tiles, hi
 }
 
 template <int R>
-bool launch_gemm_r(const SwitchParams &p, int nt, int waves, int form, int64_t n_tiles, hipStream_t s)
+bool launch_gemm_r(const SwitchParams &p, int nt, int waves, GemmForm form, int64_t n_tiles, hipStream_t s)
 {
     return waves == 8 ? launch_gemm_rw<R, 8>(p, nt, form, n_tiles, s) : launch_gemm_rw<R, 4>(p, nt, form, n_tiles, s);
 }
 
-// nt = term bucket (1, 2, 4 or 8); waves = 4 or 8 per workgroup (tile 64 x 64 waves); form = forced form or 0
-bool launch_gemm(const SwitchParams &p, int nt, int waves, int form, int64_t n_tiles, hipStream_t s)
+// nt = term bucket (1, 2, 4 or 8); waves = 4 or 8 per workgroup (tile 64 x 64 waves)
+bool launch_gemm(const SwitchParams &p, int nt, int waves, GemmForm form, int64_t n_tiles, hipStream_t s)
 {
     switch (p.r) {
     case 4: return launch_gemm_r<4>(p, nt, waves, form, n_tiles, s);
@@ -247,8 +261,11 @@ void free_tables(adafuse_ctx *c)
 {
     if (c->d_mats) (void)hipFree(c->d_mats);
     if (c->d_tiles) (void)hipFree(c->d_tiles);
+    if (c->d_tall) (void)hipFree(c->d_tall);
     c->d_mats = nullptr;
     c->d_tiles = nullptr;
+    c->d_tall = nullptr;
+    c->n_tall = 0;
 }
 
 // Waves per workgroup of the rank-looped kernel when the caller leaves the choice to the library:
@@ -259,7 +276,7 @@ void free_tables(adafuse_ctx *c)
 int auto_gemm_waves(const adafuse_ctx *c)
 {
     const int nt = terms_bucket(max_terms(c));
-    if (pick_gemm_form(c->r, nt, c->opt_form) != kFormUnrolled) return 4;
+    if (pick_gemm_form(c->r, nt, c->opt_form, false) != kFormUnrolled) return 4;
     return host::odd_pitch_share(c->mats) > 0.75 ? 8 : 4;
 }
 
@@ -286,8 +303,14 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
     plan.inner = (size_t)max_terms(c) * c->r;
     plan.panel_bytes = (size_t)std::max(1, c->opt_panel_kb) * 1024;
     plan.xcd_run = c->opt_xcd_run;
-    host::Tables t;
+    host::Tables t, tall;
     if (!host::build_tile_tables(c->mats, plan, t)) return ADAFUSE_ERR_SHAPE;
+    const bool want_tall = kernel == ADAFUSE_KERNEL_GEMM && gemm_waves == 4;
+    if (want_tall) {  // the same walk in tiles of 128 rows
+        host::TablePlan tp = plan;
+        tp.tile_rows = kTallTileRows;
+        if (!host::build_tile_tables(c->mats, tp, tall)) return ADAFUSE_ERR_SHAPE;
+    }
 
     int device = -1;
     if (hipGetDevice(&device) != hipSuccess) return ADAFUSE_ERR_HIP;
@@ -300,15 +323,25 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
         (void)hipFree(dm);
         return ADAFUSE_ERR_HIP;
     }
-    if (hipMemcpy(dm, t.mats.data(), t.mats.size() * sizeof(MatDev), hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(dt, t.tiles.data(), t.tiles.size() * sizeof(TileDev), hipMemcpyHostToDevice) != hipSuccess) {
+    TileDev *dtall = nullptr;
+    if (want_tall && hipMalloc(&dtall, (size_t)tall.n_tiles * sizeof(TileDev)) != hipSuccess) {
         (void)hipFree(dm);
         (void)hipFree(dt);
+        return ADAFUSE_ERR_HIP;
+    }
+    if (hipMemcpy(dm, t.mats.data(), t.mats.size() * sizeof(MatDev), hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(dt, t.tiles.data(), t.tiles.size() * sizeof(TileDev), hipMemcpyHostToDevice) != hipSuccess ||
+        (want_tall && hipMemcpy(dtall, tall.tiles.data(), (size_t)tall.n_tiles * sizeof(TileDev), hipMemcpyHostToDevice) != hipSuccess)) {
+        (void)hipFree(dm);
+        (void)hipFree(dt);
+        if (dtall) (void)hipFree(dtall);
         return ADAFUSE_ERR_HIP;
     }
     free_tables(c);
     c->d_mats = dm;
     c->d_tiles = dt;
+    c->d_tall = dtall;
+    c->n_tall = want_tall ? tall.n_tiles : 0;
     c->device = device;
     c->scratch = static_cast<float *>(scratch_ptr);
     c->kernel = kernel;
@@ -386,7 +419,7 @@ adafuse_status adafuse_set_option(adafuse_ctx *ctx, int32_t option, int32_t valu
         ctx->opt_waves = value;
         break;
     case ADAFUSE_OPT_GEMM_FORM:
-        if (value != 0 && value != 1 && value != 3) return ADAFUSE_ERR_ARG;
+        if (value != 0 && value != 1 && value != 3 && value != 4) return ADAFUSE_ERR_ARG;
         ctx->opt_form = value;
         break;
     case ADAFUSE_OPT_XCD_RUN:
@@ -496,8 +529,16 @@ adafuse_status switch_launches(adafuse_ctx *ctx, const int32_t *idx_prev, const 
             });
             if (!launched) return ADAFUSE_ERR_ARG;
         } else if (ctx->kernel == ADAFUSE_KERNEL_GEMM) {
-            // the copy (nothing selected) runs through the one-term instance
-            if (!launch_gemm(p, terms_bucket(n_terms > 0 ? n_terms : 1), ctx->gemm_waves, ctx->opt_form, count, s)) return ADAFUSE_ERR_ARG;
+            // the copy (nothing selected) runs through the one-term instance of the unrolled form: there is
+            // nothing to overlap, and W first, through registers, is the faster copy
+            const int nt = terms_bucket(n_terms > 0 ? n_terms : 1);
+            GemmForm form = copy_only ? kFormUnrolled : pick_gemm_form(ctx->r, nt, ctx->opt_form, !per_matrix && ctx->d_tall != nullptr);
+            if (form == kFormTall) {  // its own table: the whole model in tiles of 128 rows
+                p.tiles = ctx->d_tall;
+                if (!launch_gemm(p, nt, 4, form, ctx->n_tall, s)) return ADAFUSE_ERR_ARG;
+            } else if (!launch_gemm(p, nt, ctx->gemm_waves, form, count, s)) {
+                return ADAFUSE_ERR_ARG;
+            }
         } else {
             hipLaunchKernelGGL(switch_valu_kernel, dim3((unsigned)count), dim3(256), valu_lds, s, p);
         }
@@ -651,7 +692,11 @@ const char *adafuse_switch_kernel_name(const adafuse_ctx *ctx, int32_t k, int32_
     case ADAFUSE_KERNEL_MFMA: return copy_only ? "switch_copy_kernel" : "switch_mfma_kernel";
     case ADAFUSE_KERNEL_GEMM:
         if (copy_only) return "switch_gemm_kernel";
-        return pick_gemm_form(ctx->r, terms_bucket(n_terms), ctx->opt_form) == kFormOverlap ? "switch_gemm_overlap_kernel" : "switch_gemm_kernel";
+        switch (pick_gemm_form(ctx->r, terms_bucket(n_terms), ctx->opt_form, ctx->d_tall != nullptr)) {
+        case kFormTall: return "switch_gemm_tall_kernel";
+        case kFormOverlap: return "switch_gemm_overlap_kernel";
+        default: return "switch_gemm_kernel";
+        }
     default: return "switch_valu_kernel";
     }
 }

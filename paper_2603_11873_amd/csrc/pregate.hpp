@@ -5,9 +5,9 @@
 // w, w+4, ..., two at a time: 128-bit bf16 loads of the hidden row and the router
 // rows, exact bf16 x bf16 products in fp32, accumulation in fp64 (full rate on this
 // chip and free at this size), butterfly reduction across the wave.  The fp32-rounded
-// logits go to LDS; thread 0 then takes k rounds of arg-max (strict '>' so the
-// lowest index wins a tie) and the softmax.  The whole step is a few KB of
-// traffic and is bound by launch latency.
+// logits go to LDS; wave 0 then holds one expert per lane and takes k rounds of a
+// wave-wide arg-max (the lowest index wins a tie) and the softmax.  The whole step
+// is a few KB of traffic and is bound by launch latency.
 #pragma once
 #include "device_types.hpp"
 
@@ -82,31 +82,46 @@ __global__ __launch_bounds__(256) void pregate_kernel(PregateParams p)
     }
     __syncthreads();
 
-    if (threadIdx.x == 0) {
-        int sel[kMaxTopK];
-        uint64_t taken = 0;
-        for (int j = 0; j < p.k; ++j) {
-            int best = -1;
-            float bv = 0.0f;
-            for (int e = 0; e < p.E; ++e) {
-                if ((taken >> e) & 1ull) continue;
-                const float v = s_logit[e];
-                if (best < 0 || v > bv) { best = e; bv = v; }
-            }
-            taken |= 1ull << best;
-            sel[j] = best;
+    // Selection and softmax on wave 0, one expert per lane (E <= 64).  Round j: the wave's largest
+    // remaining logit by a butterfly of (value, index) pairs, the lower index winning a tie; lane j
+    // keeps round j's result.  The sums of the softmax are taken in index order (the order a
+    // sequential loop would use), so the gates do not depend on how the lanes are combined.
+    if (wave != 0) return;
+    const bool valid = lane < p.E;
+    const float mine = valid ? s_logit[lane] : 0.0f;
+    bool taken = !valid;
+    int sel = 0;
+    float val = 0.0f;
+    for (int j = 0; j < p.k; ++j) {
+        float bv = mine;
+        int be = taken ? 0x7fffffff : lane;   // a lane that is out of the running loses against any that is in
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float ov = __shfl_xor(bv, off, 64);
+            const int oe = __shfl_xor(be, off, 64);
+            const bool other_in = oe != 0x7fffffff, self_in = be != 0x7fffffff;
+            const bool take = other_in && (!self_in || ov > bv || (ov == bv && oe < be));
+            bv = take ? ov : bv;
+            be = take ? oe : be;
         }
-        const double mx = (double)s_logit[sel[0]];
-        double denom = 0.0;
-        if (p.gate_norm == 0) {
-            for (int j = 0; j < p.k; ++j) denom += exp((double)s_logit[sel[j]] - mx);
-        } else {
-            for (int e = 0; e < p.E; ++e) denom += exp((double)s_logit[e] - mx);
+        if (lane == be) taken = true;
+        if (lane == j) {
+            sel = be;
+            val = bv;
         }
-        for (int j = 0; j < p.k; ++j) {
-            p.idx[(size_t)t * p.k + j] = sel[j];
-            p.gates[(size_t)t * p.k + j] = (float)(exp((double)s_logit[sel[j]] - mx) / denom);
-        }
+    }
+    const double mx = (double)__shfl(val, 0, 64);  // the overall maximum is selected first
+    const double ex_sel = exp((double)val - mx);   // lanes j < k: the selected logits
+    double denom = 0.0;
+    if (p.gate_norm == 0) {
+        for (int j = 0; j < p.k; ++j) denom += __shfl(ex_sel, j, 64);
+    } else {
+        const double ex_all = exp((double)mine - mx);
+        for (int e = 0; e < p.E; ++e) denom += __shfl(ex_all, e, 64);
+    }
+    if (lane < p.k) {
+        p.idx[(size_t)t * p.k + lane] = sel;
+        p.gates[(size_t)t * p.k + lane] = (float)(ex_sel / denom);
     }
 }
 

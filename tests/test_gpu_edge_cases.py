@@ -88,10 +88,12 @@ def test_nothing_outside_the_selected_slices_reaches_the_update(oracle, kernel, 
 
 
 @pytest.mark.parametrize("r", [4, 8, 16])
-def test_padded_ranks_in_the_eight_term_form(oracle, r):
+@pytest.mark.parametrize("form,name", [(4, "switch_gemm_tall_kernel"), (0, "switch_gemm_overlap_kernel")])
+def test_padded_ranks_in_the_eight_term_form(oracle, r, form, name):
     """In place with top-4: a SWAP carries eight terms, which the default kernel runs in its
-    overlapped form (operands fetched 16 bytes per lane, rank padding through the descriptor).
-    Previous and next token share the bank's last expert; three experts in between are poison."""
+    64-row overlapped form and, on request, in its 128-row form (both fetch the operands 16 bytes
+    per lane, with the rank padding through the descriptor).  Previous and next token share the
+    bank's last expert; three experts in between are poison."""
     g = torch.Generator().manual_seed(7 + r)
     out, in_, E = 190, 264, 10
     prev = (np.array([0, 2, 4, 9], np.int32), np.array([0.4, 0.3, 0.2, 0.1], np.float32))
@@ -100,7 +102,8 @@ def test_padded_ranks_in_the_eight_term_form(oracle, r):
     before = oracle.merge(wlmod.bits(base), wlmod.bits(a), wlmod.bits(b), prev[0], prev[1], 2.0)
     w, w_big = _guarded(wlmod.from_bits(before, "cuda:0"))
     ctx = af.Context([(w, w, a, b)], 4)
-    assert ctx.switch_kernel_name(4, af.SWAP) == "switch_gemm_overlap_kernel"
+    ctx.set_option(af.OPT_GEMM_FORM, form)
+    assert ctx.switch_kernel_name(4, af.SWAP) == name
     dev = lambda x: torch.as_tensor(x, device="cuda:0")
     ctx.fused_switch(dev(prev[0]), dev(prev[1]), dev(nxt[0]), dev(nxt[1]), 4, 2.0, af.SWAP)
     _sync()

@@ -5,8 +5,10 @@ Tolerance.  The device forms every output element as an fp32 sum of exact bf16 x
 (the inner dimension in four parts added in a fixed order), and carries the scaled
 down-projection s g (A x) as a pair of bf16 values (relative remainder below 2^-17).  With
 mag = sum_i |W||x| + sum_j |s g_j| sum_rho |B_j| (sum_i |A_j||x|) the worst case is
-(in / 4 + r + 8) 2^-24 mag + 2^-17 (adapter part); independent roundings add like a random walk,
-so what is asserted is 2e-6 mag (measured: 3e-8 on the 7B shapes, 1.4e-7 on the toy).
+(in / 4 + r + 8) 2^-24 mag + 2^-17 mag_adapter (the second term of mag); the fp32 roundings are
+independent and add like a random walk, so what is asserted is 2e-6 mag + 2^-17 mag_adapter
+(measured: 3e-8 mag on the 7B shapes, 1.4e-7 on the toy; the pair's remainder only shows where
+the input width is a handful of elements and the adapters are most of the result).
 """
 import numpy as np
 import pytest
@@ -23,11 +25,13 @@ NAN_BITS = 0x7FC1
 
 
 def _magnitude(w, a, b, idx_t, gates_t, scale, x_t):
+    """(mag, mag_adapter) per output row: sums of absolute values of everything that enters it."""
     f = lambda v: np.abs(wlmod.from_bits(v).double().numpy())
-    mag = f(w) @ np.abs(x_t)
+    base = f(w) @ np.abs(x_t)
+    ad = np.zeros_like(base)
     for e, g in zip(idx_t, gates_t):
-        mag = mag + abs(float(scale) * float(g)) * (f(b[e]) @ (f(a[e]) @ np.abs(x_t)))
-    return mag
+        ad = ad + abs(float(scale) * float(g)) * (f(b[e]) @ (f(a[e]) @ np.abs(x_t)))
+    return base + ad, ad
 
 
 def _check(oracle, mat, x, idx, gates, scale, y, tokens):
@@ -40,9 +44,9 @@ def _check(oracle, mat, x, idx, gates, scale, y, tokens):
     xs = x.double().cpu().numpy()
     worst = 0.0
     for row, t in zip(want, tokens):
-        mag = _magnitude(w_h, a_h, b_h, idx[t], gates[t], scale, xs[t])
+        mag, mag_ad = _magnitude(w_h, a_h, b_h, idx[t], gates[t], scale, xs[t])
         err = np.abs(got[t] - row)
-        assert np.all(err <= RTOL_MAG * mag), (t, float(np.max(err / mag)))
+        assert np.all(err <= RTOL_MAG * mag + 2.0 ** -17 * mag_ad), (t, float(np.max(err / mag)))
         worst = max(worst, float(np.max(err / mag)))
     return worst
 
