@@ -73,6 +73,12 @@ __device__ __forceinline__ uint4_t ld_buffer_b128(__amdgpu_buffer_rsrc_t rsrc, u
     return __builtin_bit_cast(uint4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)lane_off, (int)uniform_off, 0));
 }
 
+// Store through a buffer descriptor, streaming (non-temporal); an offset beyond the descriptor's size is dropped.
+__device__ __forceinline__ void st_buffer_b128_nt(uint4_t v, __amdgpu_buffer_rsrc_t rsrc, uint32_t lane_off)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, (int)lane_off, 0, 2 /* non-temporal */);
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }

@@ -124,16 +124,20 @@ __device__ __forceinline__ int opaque_copy(int v)
     asm volatile("" : "+v"(v));
     return v;
 }
-// Write-back: the pieces go out the way they came in; nothing beyond the edge.
+// Write-back: the pieces go out the way they came in.  Every thread issues all of its stores,
+// through a buffer descriptor on the tile's origin: a piece beyond the matrix edge is pointed at an
+// offset outside the descriptor, where the hardware drops it.  No store sits in a branch (a branch
+// per store costs a few percent of the whole launch: the compiler closes each with its own waits).
 template <int TC, int NTHR, int WQ>
-__device__ __forceinline__ void w_tile_store(uint16_t (*s_w)[TC], const TileDev &tile, int tid)
+__device__ __forceinline__ void w_tile_store(uint16_t (*s_w)[TC], const TileDev &tile, int tid, int row_base = 0)
 {
+    const __amdgpu_buffer_rsrc_t rs = make_buffer(tile.w_dst, 0xfffffff0u);
 #pragma unroll
     for (int i = 0; i < WQ; ++i) {
         const int q = tid + NTHR * i;
-        const int row = q / (TC / 8), pc = q % (TC / 8);
-        if (row < tile.rows_left && 8 * pc < tile.cols_left)
-            st_global_nt(*w_slot<TC>(s_w, row, pc), reinterpret_cast<uint4_t *>(tile.w_dst + (size_t)row * tile.ldw + 8 * pc));
+        const int row = row_base + q / (TC / 8), pc = q % (TC / 8);
+        const uint32_t off = row < tile.rows_left && 8 * pc < tile.cols_left ? 2u * ((uint32_t)row * (uint32_t)tile.ldw + 8u * (uint32_t)pc) : 0xfffffff8u;
+        st_buffer_b128_nt(*w_slot<TC>(s_w, row, pc), rs, off);
     }
 }
 

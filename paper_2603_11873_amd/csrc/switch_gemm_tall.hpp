@@ -196,16 +196,7 @@ __global__ __launch_bounds__(256) void switch_gemm_tall_kernel(SwitchParams p)
         if (c_last != 0.0f) w_tile_update_grouped<TC>(s_w + HR * half, acc, c_last, lcol0, n, h);
         lds_barrier();
         // write-back of this half: the pieces go out the way they came in
-        {
-            const int t2 = opaque_copy(tid);
-#pragma unroll
-            for (int i = 0; i < WQ; ++i) {
-                const int q = t2 + NTHR * i;
-                const int row = HR * half + q / (TC / 8), pc = q % (TC / 8);
-                if (row < rows_left && 8 * pc < cols_left)
-                    st_global_nt(*w_slot<TC>(s_w, row, pc), reinterpret_cast<uint4_t *>(tile.w_dst + (size_t)row * tile.ldw + 8 * pc));
-            }
-        }
+        w_tile_store<TC, NTHR, WQ>(s_w, tile, opaque_copy(tid), HR * half);
     }
 }
 
