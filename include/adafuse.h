@@ -271,15 +271,18 @@ adafuse_status adafuse_forward_dynamic(adafuse_ctx *ctx, const int32_t *idx, con
  *          twice for a token counts twice (its gates add).
  * y        DEVICE fp32 [T][out], contiguous, 16-byte aligned; every element is written once
  *          (no accumulation into previous contents, no atomics: the same bits on every run)
- * workspace  DEVICE, 16-byte aligned, at least 4 * T * k * max(r, 8) bytes (workspace_bytes is
- *          checked): the scaled down-projections s g A x of every (token, selection) as two
- *          bf16 planes (value and rounding remainder, 16 significant bits).  Owned by the
- *          caller; its previous contents do not matter and nothing in it needs clearing.
- * Arithmetic: bf16 operands on the matrix cores, fp32 accumulation; the inner dimension of
- * each output element is summed in four fixed parts that are added in a fixed order.
- * Two launches on `hip_stream` (down projection; base product with the up projection as
- * further inner dimension), no allocation, no synchronisation.  Needs an out-of-place
- * context (the base weights must be unmodified).
+ * workspace  DEVICE, 16-byte aligned, at least adafuse_prefill_workspace_bytes() bytes
+ *          (workspace_bytes is checked): the scaled down-projections s g A x of every (token,
+ *          selection) as two bf16 planes (value and rounding remainder, 16 significant bits),
+ *          and the fp32 parts of the products whose inner dimension is split across
+ *          workgroups (few tokens leave too few tiles to fill the chip).  Owned by the caller;
+ *          its previous contents do not matter and nothing in it needs clearing.
+ * Arithmetic: bf16 operands on the matrix cores, fp32 accumulation; the parts of a split inner
+ * dimension are added in a fixed order: the same bits on every run.
+ * Three or four launches on `hip_stream` (down projection over the whole bank, gating, base
+ * product with the up projection as further inner dimension, sum of the parts), no
+ * allocation, no synchronisation.  Needs an out-of-place context (the base weights must be
+ * unmodified).
  * Errors: NULL pointer -> ERR_NULL; mat, T < 0, k out of range, in-place context, workspace
  * too small, wrong device -> ERR_ARG; misaligned x / y / workspace -> ERR_ALIGN;
  * T * in or T * k * r beyond 2^30 elements -> ERR_SHAPE.  T == 0 is a no-op.
@@ -287,6 +290,11 @@ adafuse_status adafuse_forward_dynamic(adafuse_ctx *ctx, const int32_t *idx, con
 adafuse_status adafuse_prefill(adafuse_ctx *ctx, int32_t mat, const void *x, int32_t T,
                                const int32_t *idx, const float *gates, int32_t k, float scale,
                                float *y, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of workspace adafuse_prefill needs for T tokens with k selections each through matrix
+ * `mat` (HOST result in *bytes; 0 for T == 0).  Errors as adafuse_prefill's argument checks. */
+adafuse_status adafuse_prefill_workspace_bytes(const adafuse_ctx *ctx, int32_t mat, int32_t T, int32_t k,
+                                               size_t *bytes);
 
 /*
  * adafuse_forward_dynamic for callers that cannot allocate device memory or hand over a

@@ -13,7 +13,7 @@ OPT_KERNEL, OPT_GEMM_WAVES, OPT_GEMM_FORM, OPT_XCD_RUN, OPT_PANEL_KB, OPT_MFMA_S
 
 EXPORTS = ["adafuse_create", "adafuse_destroy", "adafuse_set_option", "adafuse_get_info",
            "adafuse_pregate", "adafuse_fused_switch", "adafuse_switch_per_matrix", "adafuse_forward_merged", "adafuse_forward_dynamic",
-           "adafuse_forward_dynamic_static", "adafuse_prefill", "adafuse_switch_kernel_name", "adafuse_status_string"]
+           "adafuse_forward_dynamic_static", "adafuse_prefill", "adafuse_prefill_workspace_bytes", "adafuse_switch_kernel_name", "adafuse_status_string"]
 
 
 class AdafuseError(RuntimeError):
@@ -72,6 +72,8 @@ def load_library():
     L.adafuse_forward_dynamic_static.argtypes = [vp, C.POINTER(i32), C.POINTER(f32), i32, f32, vp, vp, vp]
     L.adafuse_prefill.restype = i32
     L.adafuse_prefill.argtypes = [vp, i32, vp, i32, vp, vp, i32, f32, vp, vp, C.c_size_t, vp]
+    L.adafuse_prefill_workspace_bytes.restype = i32
+    L.adafuse_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_size_t)]
     L.adafuse_switch_kernel_name.restype = C.c_char_p
     L.adafuse_switch_kernel_name.argtypes = [vp, i32, i32]
     L.adafuse_status_string.restype = C.c_char_p
@@ -209,6 +211,14 @@ class Context:
         if st != 0:
             raise AdafuseError(st, "adafuse_forward_dynamic_static")
 
+    def prefill_workspace_bytes(self, mat, T, k):
+        """adafuse_prefill_workspace_bytes"""
+        n = C.c_size_t(0)
+        st = load_library().adafuse_prefill_workspace_bytes(self._h, mat, T, k, C.byref(n))
+        if st != 0:
+            raise AdafuseError(st, "adafuse_prefill_workspace_bytes")
+        return int(n.value)
+
     def prefill(self, mat, x, idx, gates, scale, y=None, workspace=None, stream=None):
         """adafuse_prefill: x bf16 [T][in], idx int32 [T][k], gates fp32 [T][k] (device) -> y fp32 [T][out]."""
         import torch
@@ -219,7 +229,7 @@ class Context:
         if y is None:
             y = torch.empty((T, out), dtype=torch.float32, device=x.device)
         if workspace is None:
-            workspace = torch.empty(max(16, 4 * T * k * max(self.r, 8)), dtype=torch.uint8, device=x.device)
+            workspace = torch.empty(max(16, self.prefill_workspace_bytes(mat, T, k)), dtype=torch.uint8, device=x.device)
         st = load_library().adafuse_prefill(self._h, mat, _ptr(x), T, _ptr(idx), _ptr(gates), k, scale, _ptr(y),
                                             _ptr(workspace), workspace.numel() * workspace.element_size(),
                                             _stream_handle(stream))

@@ -638,6 +638,65 @@ adafuse_status adafuse_forward_dynamic_static(adafuse_ctx *ctx, const int32_t *i
     return forward_dynamic_launches(ctx, idx_host, gates_host, k, scale, x, y, ctx->scratch, hip_stream);
 }
 
+namespace {
+
+// How one product of adafuse_prefill is cut: tiles of 128 tokens x 256 rows, and the inner dimension in
+// `splits` parts of `chunks_per_split` chunks of 64, so that a launch has at least one workgroup per CU
+// (one is resident at a time: 144 KB of LDS).  Every part costs T x rows x 8 bytes of traffic on top.
+struct PrefillCut {
+    int m_tiles, strips, splits, chunks_per_split;
+};
+
+PrefillCut prefill_cut(int T, int rows, int in)
+{
+    PrefillCut c;
+    c.m_tiles = (T + kPfTileTokens - 1) / kPfTileTokens;
+    c.strips = (rows + kPfTileRows - 1) / kPfTileRows;
+    const int chunks = (in + kPfChunk - 1) / kPfChunk;
+    // as many parts as still give at most one workgroup per CU (256): one more workgroup than CUs is a
+    // second round for the whole launch; at least two chunks per part
+    int want = 256 / (c.m_tiles * c.strips);
+    want = std::max(1, std::min(want, std::min(kPfMaxSplits, chunks / 2)));
+    c.chunks_per_split = (chunks + want - 1) / want;
+    c.splits = (chunks + c.chunks_per_split - 1) / c.chunks_per_split;       // no empty part
+    return c;
+}
+
+struct PrefillPlan {
+    PrefillCut down, up;
+    int rp;
+    uint64_t plane;        // bytes of one bf16 plane of the scaled down-projections
+    uint64_t parts_bytes;  // fp32 parts of the split products (the two passes share the space)
+};
+
+PrefillPlan prefill_plan(const adafuse_ctx *ctx, const adafuse_matrix_desc &m, int T, int k)
+{
+    PrefillPlan pl;
+    pl.rp = ctx->r < 8 ? 8 : ctx->r;  // a slot holds whole 16-byte pieces
+    pl.plane = ((uint64_t)T * (uint64_t)k * (uint64_t)pl.rp * 2u + 15u) & ~15ull;
+    pl.down = prefill_cut(T, ctx->E * ctx->r, m.in);
+    pl.up = prefill_cut(T, m.out, m.in);
+    const uint64_t down_parts = (uint64_t)pl.down.splits * T * ctx->E * ctx->r * 4u;   // U is always a temporary
+    const uint64_t up_parts = pl.up.splits > 1 ? (uint64_t)pl.up.splits * T * m.out * 4u : 0u;
+    pl.parts_bytes = std::max(down_parts, up_parts);
+    return pl;
+}
+
+}  // namespace
+
+adafuse_status adafuse_prefill_workspace_bytes(const adafuse_ctx *ctx, int32_t mat, int32_t T, int32_t k, size_t *bytes)
+{
+    if (!ctx || !bytes) return ADAFUSE_ERR_NULL;
+    if (mat < 0 || mat >= (int32_t)ctx->mats.size() || T < 0 || k < 1 || k > ctx->k_max) return ADAFUSE_ERR_ARG;
+    if (T == 0) {
+        *bytes = 0;
+        return ADAFUSE_OK;
+    }
+    const PrefillPlan pl = prefill_plan(ctx, ctx->mats[(size_t)mat], T, k);
+    *bytes = (size_t)(2 * pl.plane + pl.parts_bytes);
+    return ADAFUSE_OK;
+}
+
 adafuse_status adafuse_prefill(adafuse_ctx *ctx, int32_t mat, const void *x, int32_t T, const int32_t *idx,
                                const float *gates, int32_t k, float scale, float *y, void *workspace,
                                size_t workspace_bytes, void *hip_stream)
@@ -649,33 +708,36 @@ adafuse_status adafuse_prefill(adafuse_ctx *ctx, int32_t mat, const void *x, int
     if (!x || !idx || !gates || !y || !workspace) return ADAFUSE_ERR_NULL;
     if (!aligned16(x) || !aligned16(y) || !aligned16(workspace)) return ADAFUSE_ERR_ALIGN;
     const adafuse_matrix_desc &m = ctx->mats[(size_t)mat];
-    const int rp = ctx->r < 8 ? 8 : ctx->r;  // a slot holds whole 16-byte pieces
-    const uint64_t plane = (uint64_t)T * (uint64_t)k * (uint64_t)rp * 2u;
-    if (workspace_bytes < 2 * plane) return ADAFUSE_ERR_ARG;
+    const PrefillPlan pl = prefill_plan(ctx, m, T, k);
+    if (workspace_bytes < 2 * pl.plane + pl.parts_bytes) return ADAFUSE_ERR_ARG;
     // the kernels address X and the workspace planes through 32-bit descriptors and offsets
-    if ((uint64_t)T * (uint64_t)m.in * 2u >= (1ull << 31) || plane >= (1ull << 31)) return ADAFUSE_ERR_SHAPE;
+    if ((uint64_t)T * (uint64_t)m.in * 2u >= (1ull << 31) || pl.plane >= (1ull << 31)) return ADAFUSE_ERR_SHAPE;
     if (!on_ctx_device(ctx)) return ADAFUSE_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    PrefillParams p{static_cast<const uint16_t *>(m.w_base), static_cast<const uint16_t *>(m.a_bank),
-                    static_cast<const uint16_t *>(m.b_bank), static_cast<const uint16_t *>(x), idx, gates, y,
-                    static_cast<uint16_t *>(workspace), static_cast<uint16_t *>(workspace) + plane / 2,
-                    m.out, m.in, m.ldw, T, ctx->E, ctx->r, rp, k, scale};
-    const dim3 down_grid((unsigned)((T + 31) / 32), (unsigned)ctx->E);
-    if (ctx->r <= 32)
-        hipLaunchKernelGGL(prefill_down_kernel<1>, down_grid, dim3(256), 0, s, p);
-    else if (ctx->r == 64)
-        hipLaunchKernelGGL(prefill_down_kernel<2>, down_grid, dim3(256), 0, s, p);
-    else
-        hipLaunchKernelGGL(prefill_down_kernel<4>, down_grid, dim3(256), 0, s, p);
-    // 128 tokens per workgroup once that still fills the chip several times over, else 64
-    const int strips = (m.out + 31) / 32;
-    const bool big = (int64_t)((T + 127) / 128) * strips >= 1024;
-    const int m_tiles = big ? (T + 127) / 128 : (T + 63) / 64;
-    const unsigned up_grid = (unsigned)(((strips + 7) / 8) * 8 * m_tiles);
-    if (big)
-        hipLaunchKernelGGL(prefill_up_kernel<4>, dim3(up_grid), dim3(256), 0, s, p, m_tiles, strips);
-    else
-        hipLaunchKernelGGL(prefill_up_kernel<2>, dim3(up_grid), dim3(256), 0, s, p, m_tiles, strips);
+    uint16_t *z_hi = static_cast<uint16_t *>(workspace);
+    uint16_t *z_lo = z_hi + pl.plane / 2;
+    float *parts = reinterpret_cast<float *>(z_lo + pl.plane / 2);
+    const uint16_t *xp = static_cast<const uint16_t *>(x);
+    auto grid_of = [](const PrefillCut &c) { return dim3((unsigned)(((c.strips * c.splits + 7) / 8) * 8 * c.m_tiles)); };
+
+    // 1. U = X A^T over the whole bank, in parts
+    PrefillGemm down{static_cast<const uint16_t *>(m.a_bank), xp, parts, ctx->E * ctx->r, m.in, m.in, T,
+                     pl.down.splits, pl.down.chunks_per_split, pl.down.m_tiles, pl.down.strips,
+                     nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0};
+    hipLaunchKernelGGL(prefill_gemm_kernel, grid_of(pl.down), dim3(256), 0, s, down);
+    // 2. the selected experts' columns, scaled by s g, as bf16 pairs
+    PrefillGate gate{parts, idx, gates, z_hi, z_lo, T, ctx->E, ctx->r, pl.rp, k, pl.down.splits, scale};
+    const int64_t n_z = (int64_t)T * k * pl.rp;
+    hipLaunchKernelGGL(prefill_gate_kernel, dim3((unsigned)((n_z + 255) / 256)), dim3(256), 0, s, gate);
+    // 3. X W^T with the adapters as further inner dimension; 4. its parts summed
+    PrefillGemm up{static_cast<const uint16_t *>(m.w_base), xp, pl.up.splits > 1 ? parts : y, m.out, m.ldw, m.in, T,
+                   pl.up.splits, pl.up.chunks_per_split, pl.up.m_tiles, pl.up.strips,
+                   static_cast<const uint16_t *>(m.b_bank), idx, z_hi, z_lo, ctx->E, ctx->r, pl.rp, k};
+    hipLaunchKernelGGL(prefill_gemm_kernel, grid_of(pl.up), dim3(256), 0, s, up);
+    if (pl.up.splits > 1) {
+        const int64_t n_y = (int64_t)T * m.out;
+        hipLaunchKernelGGL(prefill_sum_kernel, dim3((unsigned)((n_y + 1023) / 1024)), dim3(256), 0, s, parts, y, n_y, pl.up.splits);
+    }
     return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
 }
 

@@ -2,27 +2,35 @@
 // decision (section "Decoding Phase", prefill paragraph: one merged weight cannot serve
 // tokens that selected different experts, so the adapters stay un-merged here, Eq.2):
 //   Y[t] = W_base x_t + s * sum_j g_{t,j} * B_{e_{t,j}} (A_{e_{t,j}} x_t),   t < T.
-// Two kernels, both on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation):
+// One matrix-core product kernel (v_mfma_f32_32x32x16_bf16, fp32 accumulation), used twice,
+// and two small element-wise kernels:
 //
-//   prefill_down_kernel   one workgroup per (block of 32 tokens, expert).  A workgroup whose
-//       expert none of its tokens selected returns at once; the others form
-//       Z[rho][t] = sum_i A_e[rho][i] x_t[i] for the whole block (a dense 32-token product:
-//       tokens are grouped by position, the expert decides which blocks run), scale the
-//       columns of the tokens that selected e by s * g and store them as a pair of bf16
-//       planes hi + lo (16 significant bits) in the slot of that (token, selection).
-//   prefill_up_kernel     one workgroup per (tile of 32 MB tokens, strip of 32 output rows):
-//       the base product over the whole input width, then, for every expert some token of
-//       the tile selected, k-steps over the rank with the token's scaled Z (zero for tokens
-//       that did not select it) against B_e's rows -- the adapter is just more inner
-//       dimension of the same product, so Y is written once, no atomics, same bits every run.
+//   1. prefill_gemm_kernel on the A bank seen as one [E r][in] matrix: U = X A^T for ALL
+//      experts (dense: the bank is a fraction of W, and with more than a few dozen tokens
+//      every expert is selected by some token of a tile anyway).
+//   2. prefill_gate_kernel: for every (token, selection) the expert's r columns of U times
+//      s * g, stored as a pair of bf16 planes hi + lo (16 significant bits), zero padded to
+//      a multiple of 8; a repeated selection of an expert is folded into the first.
+//   3. prefill_gemm_kernel on W_base: X W^T, and in the same accumulators, for every expert
+//      some token of the tile selected, k-steps over the rank with the token's scaled
+//      down-projection (zero for tokens that did not select it) against B_e's rows -- the
+//      adapter is just more inner dimension of the same product.
+//   4. prefill_sum_kernel (only when the inner dimension was split): the parts, in order.
 //
-// Both split the inner dimension over the four waves of a workgroup (each wave streams its
-// share of the rows' k-range straight from global memory into matrix-core operands: a lane
-// holds 8 consecutive inner indices of one row, one 16-byte load) and add the four partial
-// results in a fixed order through LDS.  W is read once per token tile; X and the banks come
-// out of L2.  Operand loads use buffer descriptors with the "beyond the edge" lanes pointed
-// outside the descriptor, so ragged T, out, in and padded ranks read as zero, never as
-// whatever sits behind the row.
+// The product kernel: a workgroup (4 waves side by side, 128 tokens x 64 rows each) owns 128 tokens
+// x 256 output rows and a range of the inner dimension; chunks of 64 inner indices of both
+// operands go straight into LDS (buffer_load ... lds, row-contiguous 128-byte lines: a wave
+// instruction moves 8 whole lines) in three stages -- two chunks, 64 KB of the matrix, in flight per
+// CU while a third is multiplied: at a hundred tokens the product is bound by streaming the matrix
+// once, and what is in flight decides the rate -- and each wave reads its operands from there in the matrix-core layout (the
+// 16-byte pieces of a line are permuted by the row number, so both the line-wise fill and the
+// column-of-pieces reads are conflict-free).  Loading operands straight from global memory in
+// the matrix-core layout (one row per lane) was the first version: 32 cache lines per wave
+// instruction, four times the address work in the texture path, and 10 x off the roofline.
+// With few tokens a launch has too few tiles to fill the chip, so the inner dimension is split
+// across workgroups and the parts are summed in a fixed order afterwards: no atomics, the
+// same bits on every run.  Lanes beyond T, the matrix edge or the split's range point outside
+// their buffer descriptor and read as zero.
 #pragma once
 #include "device_types.hpp"
 
@@ -30,270 +38,314 @@ namespace adafuse {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 pf_bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float pf_float16_t;
+typedef __attribute__((address_space(3))) void pf_lds_void_t;
 
-struct PrefillParams {
-    const uint16_t *w;       // [out][ldw] base weights
-    const uint16_t *a_bank;  // [E][r][in]
-    const uint16_t *b_bank;  // [E][out][r]
-    const uint16_t *x;       // [T][in]
-    const int32_t *idx;      // [T][k]
-    const float *gates;      // [T][k]
-    float *y;                // [T][out]
-    uint16_t *z_hi;          // [T][k][rp]  scaled down-projections, upper bf16 plane
-    uint16_t *z_lo;          // [T][k][rp]  ... and the bf16 rounding of what the upper plane left over
-    int32_t out, in, ldw, T, E, r, rp, k;
-    float scale;
-};
-
+constexpr int kPfTileTokens = 128;  // tokens per workgroup
+constexpr int kPfTileRows = 256;    // output rows per workgroup: 64 per wave
+constexpr int kPfChunk = 64;        // inner indices per LDS stage (one 128-byte line per row)
 constexpr uint32_t kOutside = 0xffffff00u;  // a per-lane offset no descriptor of this library covers: reads as zero
 
-__device__ __forceinline__ pf_bf16x8_t as_operand(uint4_t v) { return __builtin_bit_cast(pf_bf16x8_t, v); }
+struct PrefillGemm {
+    const uint16_t *m;       // [rows][ld] bf16: W_base, or the A bank as [E r][in]
+    const uint16_t *x;       // [T][in] bf16
+    float *out;              // [splits][T][rows] fp32 (splits == 1: the result itself)
+    int32_t rows, ld, in, T;
+    int32_t splits;          // parts of the inner dimension
+    int32_t chunks_per_split;
+    int32_t m_tiles, strips;
+    // adapters (W pass only; b_bank == nullptr: none)
+    const uint16_t *b_bank;  // [E][rows][r]
+    const int32_t *idx;      // [T][k]
+    const uint16_t *z_hi;    // [T][k][rp]
+    const uint16_t *z_lo;
+    int32_t E, r, rp, k;
+};
 
+__device__ __forceinline__ pf_bf16x8_t as_operand(uint4_t v) { return __builtin_bit_cast(pf_bf16x8_t, v); }
 __device__ __forceinline__ int clamp_expert(int e, int E) { return e < 0 ? 0 : (e >= E ? E - 1 : e); }
 
 // Experts selected by any of the tokens [t0, t0 + n_tok) as a bit mask (E <= 64); every wave
 // computes it for itself, lane l looking at tokens t0 + l, t0 + l + 64, ...
-__device__ __forceinline__ uint64_t experts_in_tile(const PrefillParams &p, int t0, int n_tok, int lane)
+__device__ __forceinline__ uint64_t experts_in_tile(const int32_t *idx, int k, int E, int T, int t0, int n_tok, int lane)
 {
     uint64_t mine = 0;
-    for (int t = t0 + lane; t < t0 + n_tok && t < p.T; t += 64)
-        for (int j = 0; j < p.k; ++j) mine |= 1ull << clamp_expert(p.idx[(size_t)t * p.k + j], p.E);
+    for (int t = t0 + lane; t < t0 + n_tok && t < T; t += 64)
+        for (int j = 0; j < k; ++j) mine |= 1ull << clamp_expert(idx[(size_t)t * k + j], E);
     uint64_t all = 0;
-    for (int e = 0; e < p.E; ++e)
+    for (int e = 0; e < E; ++e)
         if (__ballot((mine >> e) & 1ull)) all |= 1ull << e;
     return all;
 }
 
-// Partial results of waves 1..3 added to wave 0's in that order, through LDS.  NV = accumulator
-// vectors (16 floats each) per lane.  Returns with the sum in wave 0's registers.
-template <int NV>
-__device__ __forceinline__ void reduce_over_waves(pf_float16_t (&acc)[NV], float *s_part, int wave, int lane)
+// One chunk of both operands into an LDS stage: 128 token lines and 256 matrix lines of 128 bytes.
+// Wave w's instruction i fills the KB that starts at line 8 (w + 4 i); lane l delivers piece slot
+// l % 8 of line 8 (w + 4 i) + l / 8, and fetches for it the piece (slot ^ line % 8) of that row.
+// Always 12 transfers per wave: a line or piece beyond the edge (or a whole chunk beyond the part's
+// range) points outside the descriptor, fetches nothing and fills its slot with zeros.
+__device__ __forceinline__ void pf_request(uint16_t *sx, uint16_t *sm, __amdgpu_buffer_rsrc_t xr, __amdgpu_buffer_rsrc_t mr,
+                                           uint32_t in_bytes, uint32_t ld_bytes, int t0, int T, int rows_here, int k0, int k_end,
+                                           int wave, int lane)
 {
-    if (wave > 0) {
 #pragma unroll
-        for (int v = 0; v < NV; ++v)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) s_part[(((wave - 1) * NV + v) * 16 + q) * 64 + lane] = acc[v][q];
+    for (int i = 0; i < kPfTileTokens / 32; ++i) {  // X: 16 KB
+        const int line = 8 * (wave + 4 * i) + lane / 8;
+        const int k = k0 + 8 * ((lane % 8) ^ (line % 8));
+        const uint32_t off = t0 + line < T && k < k_end ? (uint32_t)(t0 + line) * in_bytes + 2u * (uint32_t)k : kOutside;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (pf_lds_void_t *)(sx + 512 * (wave + 4 * i)), 16, (int)off, 0, 0, 0);
     }
-    __syncthreads();
-    if (wave == 0) {
 #pragma unroll
-        for (int w = 0; w < 3; ++w)
+    for (int i = 0; i < kPfTileRows / 32; ++i) {  // matrix: 32 KB
+        const int line = 8 * (wave + 4 * i) + lane / 8;
+        const int k = k0 + 8 * ((lane % 8) ^ (line % 8));
+        const uint32_t off = line < rows_here && k < k_end ? (uint32_t)line * ld_bytes + 2u * (uint32_t)k : kOutside;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(mr, (pf_lds_void_t *)(sm + 512 * (wave + 4 * i)), 16, (int)off, 0, 0, 2 /* streamed once */);
+    }
+}
+constexpr int kPfRequests = kPfTileTokens / 32 + kPfTileRows / 32;  // transfers per wave and chunk
+
+// The wave's 128 tokens x 64 rows of one chunk: four k-steps, operands from LDS in the matrix-core layout.
+__device__ __forceinline__ void pf_multiply(pf_float16_t (&acc)[4][2], const uint16_t *sx, const uint16_t *sm, int wave, int n, int h)
+{
 #pragma unroll
-            for (int v = 0; v < NV; ++v)
+    for (int s = 0; s < 4; ++s) {
+        const int piece = 2 * s + h;
+        uint4_t mv[2], xv[4];
 #pragma unroll
-                for (int q = 0; q < 16; ++q) acc[v][q] += s_part[((w * NV + v) * 16 + q) * 64 + lane];
+        for (int c = 0; c < 2; ++c) {
+            const int mrow = 64 * wave + 32 * c + n;
+            mv[c] = *reinterpret_cast<const uint4_t *>(sm + 64 * mrow + 8 * (piece ^ (mrow % 8)));
+        }
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int xrow = 32 * b + n;
+            xv[b] = *reinterpret_cast<const uint4_t *>(sx + 64 * xrow + 8 * (piece ^ (xrow % 8)));
+        }
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+                acc[b][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(mv[c]), as_operand(xv[b]), acc[b][c], 0, 0, 0);
     }
 }
 
-// ---- down projection -------------------------------------------------------------------------
-// RB = blocks of 32 rank indices (1 for ranks up to 32, 2 for 64, 4 for 128).
-template <int RB>
-__global__ __launch_bounds__(256) void prefill_down_kernel(PrefillParams p)
+__global__ __launch_bounds__(256) void prefill_gemm_kernel(PrefillGemm p)
 {
-    __shared__ float s_part[3 * RB * 16 * 64];
+    // three stages (144 KB: one workgroup per CU, two chunks -- 64 KB of the matrix -- in flight while a
+    // third is multiplied), each its own pair of arrays: the compiler then knows that reading one stage
+    // does not have to wait for the transfers into the others
+    __shared__ __align__(16) uint16_t s_x0[kPfTileTokens * kPfChunk], s_x1[kPfTileTokens * kPfChunk], s_x2[kPfTileTokens * kPfChunk];
+    __shared__ __align__(16) uint16_t s_m0[kPfTileRows * kPfChunk], s_m1[kPfTileRows * kPfChunk], s_m2[kPfTileRows * kPfChunk];
+
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, h = lane >> 5;
-    const int t0 = 32 * blockIdx.x;
-    const int e = blockIdx.y;
-    const uint64_t present = experts_in_tile(p, t0, 32, lane);
-    if (!((present >> e) & 1ull)) return;  // uniform over the workgroup
-
-    const int t = t0 + n;
-    const uint32_t in_bytes = 2u * (uint32_t)p.in;
-    const __amdgpu_buffer_rsrc_t xr = make_buffer(p.x, (uint32_t)p.T * in_bytes);  // host side keeps T * in * 2 below 2^31
-    const __amdgpu_buffer_rsrc_t ar = make_buffer(p.a_bank + (size_t)e * p.r * p.in, (uint32_t)p.r * in_bytes);
-    const uint32_t xrow = t < p.T ? (uint32_t)t * in_bytes : kOutside;
-
-    pf_float16_t acc[RB];
-#pragma unroll
-    for (int b = 0; b < RB; ++b)
-#pragma unroll
-        for (int q = 0; q < 16; ++q) acc[b][q] = 0.0f;
-
-    // this wave's share of the k-steps (16 inner indices each; the last may be half a step)
-    const int steps = (p.in + 15) / 16, per = (steps + 3) / 4;
-    const int s_begin = wave * per, s_end = min(steps, s_begin + per);
-    for (int s = s_begin; s < s_end; ++s) {
-        const uint32_t kb = 2u * (uint32_t)(16 * s + 8 * h);
-        const bool k_ok = 16 * s + 8 * h < p.in;
-        const uint4_t xv = ld_buffer_b128(xr, k_ok && xrow != kOutside ? xrow + kb : kOutside, 0u);
-#pragma unroll
-        for (int b = 0; b < RB; ++b) {
-            const int rho = 32 * b + n;
-            const uint4_t av = ld_buffer_b128(ar, k_ok && rho < p.r ? (uint32_t)rho * in_bytes + kb : kOutside, 0u);
-            acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(av), as_operand(xv), acc[b], 0, 0, 0);
-        }
-    }
-    reduce_over_waves<RB>(acc, s_part, wave, lane);
-    if (wave != 0 || t >= p.T) return;
-
-    // the lane's token: coefficient of this expert (all selections of it added) and the slot that takes the result
-    int first = -1;
-    float c = 0.0f;
-    for (int j = 0; j < p.k; ++j)
-        if (clamp_expert(p.idx[(size_t)t * p.k + j], p.E) == e) {
-            if (first < 0) first = j;
-            c += p.scale * p.gates[(size_t)t * p.k + j];
-        }
-    if (first < 0) return;
-    for (int j = 0; j < p.k; ++j) {
-        if (clamp_expert(p.idx[(size_t)t * p.k + j], p.E) != e) continue;
-        const size_t slot = ((size_t)t * p.k + j) * p.rp;
-#pragma unroll
-        for (int b = 0; b < RB; ++b)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int rho = 32 * b + 8 * q + 4 * h;  // accumulator entries 4 q .. 4 q + 3 are rank indices rho .. rho + 3
-                if (rho >= p.rp) continue;
-                uint32_t hi[2] = {0u, 0u}, lo[2] = {0u, 0u};
-                if (j == first) {  // a repeated selection of the same expert is folded into the first one
-                    float zf[4], zr[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) zf[u] = c * acc[b][4 * q + u];
-                    hi[0] = pack_bf16_rne(zf[0], zf[1]);
-                    hi[1] = pack_bf16_rne(zf[2], zf[3]);
-                    zr[0] = zf[0] - bf16_lo(hi[0]);
-                    zr[1] = zf[1] - bf16_hi(hi[0]);
-                    zr[2] = zf[2] - bf16_lo(hi[1]);
-                    zr[3] = zf[3] - bf16_hi(hi[1]);
-                    lo[0] = pack_bf16_rne(zr[0], zr[1]);
-                    lo[1] = pack_bf16_rne(zr[2], zr[3]);
-                }
-                *reinterpret_cast<uint2_t *>(p.z_hi + slot + rho) = uint2_t{hi[0], hi[1]};
-                *reinterpret_cast<uint2_t *>(p.z_lo + slot + rho) = uint2_t{lo[0], lo[1]};
-            }
-    }
-}
-
-// ---- base product + up projection --------------------------------------------------------------
-// MB = blocks of 32 tokens per workgroup.  blockIdx.x enumerates (strip of 32 output rows, token
-// tile) so that the token tiles of one strip run on the same XCD (workgroup i runs on XCD i % 8):
-// the second and later token tiles find the strip's W rows in that XCD's L2.
-template <int MB>
-__global__ __launch_bounds__(256) void prefill_up_kernel(PrefillParams p, int m_tiles, int strips)
-{
-    __shared__ float s_part[3 * MB * 16 * 64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int n = lane & 31, h = lane >> 5;
-    const int xcd = blockIdx.x % 8, q_in_xcd = blockIdx.x / 8;
-    const int strip = (q_in_xcd / m_tiles) * 8 + xcd, m_tile = q_in_xcd % m_tiles;
-    if (strip >= strips) return;
-    const int o0 = 32 * strip, t0 = 32 * MB * m_tile;
-
-    const uint32_t in_bytes = 2u * (uint32_t)p.in;
-    const int o = o0 + n;
-    const int rows = min(32, p.out - o0);
-    const __amdgpu_buffer_rsrc_t wr = make_buffer(p.w + (size_t)o0 * p.ldw, (uint32_t)rows * 2u * (uint32_t)p.ldw);
+    // workgroup i runs on XCD i % 8: the token tiles of one (strip, part) follow each other on one XCD,
+    // so the second and later ones find the matrix lines in that XCD's L2
+    const int xcd = blockIdx.x % 8, q = blockIdx.x / 8;
+    const int unit = (q / p.m_tiles) * 8 + xcd, m_tile = q % p.m_tiles;
+    if (unit >= p.strips * p.splits) return;
+    const int strip = unit / p.splits, part = unit % p.splits;
+    const int o0 = kPfTileRows * strip, t0 = kPfTileTokens * m_tile;
+    const int rows_here = min(kPfTileRows, p.rows - o0);
+    const uint32_t in_bytes = 2u * (uint32_t)p.in, ld_bytes = 2u * (uint32_t)p.ld;
     const __amdgpu_buffer_rsrc_t xr = make_buffer(p.x, (uint32_t)p.T * in_bytes);
-    const uint32_t wrow = o < p.out ? (uint32_t)n * 2u * (uint32_t)p.ldw : kOutside;
-    uint32_t xrow[MB];
-#pragma unroll
-    for (int b = 0; b < MB; ++b) xrow[b] = t0 + 32 * b + n < p.T ? (uint32_t)(t0 + 32 * b + n) * in_bytes : kOutside;
+    const __amdgpu_buffer_rsrc_t mr = make_buffer(p.m + (size_t)o0 * p.ld, (uint32_t)rows_here * ld_bytes);
+    const int k_begin = part * p.chunks_per_split * kPfChunk;
+    const int k_end = min(p.in, k_begin + p.chunks_per_split * kPfChunk);
+    const int n_chunks = (k_end - k_begin + kPfChunk - 1) / kPfChunk;  // >= 1 by construction of the split
+    const bool has_rows = 64 * wave < rows_here;                       // a wave whose 64 rows are all beyond the matrix only moves data
 
-    pf_float16_t acc[MB];
+    pf_float16_t acc[4][2];
 #pragma unroll
-    for (int b = 0; b < MB; ++b)
+    for (int b = 0; b < 4; ++b)
 #pragma unroll
-        for (int q = 0; q < 16; ++q) acc[b][q] = 0.0f;
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[b][c][v] = 0.0f;
 
-    // ---- the base product: this wave's share of the k-steps, two at a time, the next pair requested
-    // before the current one is multiplied
-    const int steps = (p.in + 15) / 16, per = (steps + 3) / 4;
-    const int s_begin = wave * per, s_end = min(steps, s_begin + per);
-    constexpr int U = 2;
-    uint4_t wv[2][U], xv[2][U][MB];
-    auto request = [&](int buf, int s) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int k0 = 16 * (s + u) + 8 * h;
-            const bool k_ok = s + u < s_end && k0 < p.in;
-            const uint32_t kb = 2u * (uint32_t)k0;
-            wv[buf][u] = ld_buffer_b128(wr, k_ok && wrow != kOutside ? wrow + kb : kOutside, 0u);
-#pragma unroll
-            for (int b = 0; b < MB; ++b)
-                xv[buf][u][b] = ld_buffer_b128(xr, k_ok && xrow[b] != kOutside ? xrow[b] + kb : kOutside, 0u);
-        }
-    };
-    auto multiply = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int b = 0; b < MB; ++b)
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(wv[buf][u]), as_operand(xv[buf][u][b]), acc[b], 0, 0, 0);
-    };
-    // (a request beyond the wave's share puts every lane outside its descriptor: zeros, no memory access)
-    int s = s_begin;
-    if (s < s_end) request(0, s);
-    while (s < s_end) {
-        request(1, s + U);
-        multiply(0);
-        s += U;
-        if (s >= s_end) break;
-        request(0, s + U);
-        multiply(1);
-        s += U;
+    // Chunk c lives in stage c % 3.  Before chunk c is multiplied: wait for this wave's part of it (the
+    // kPfRequests transfers of chunk c + 1 may stay outstanding), meet -- every wave is then also done reading
+    // the stage of chunk c - 1 --, and request chunk c + 2 into that stage.
+#define ADAFUSE_PF_STEP(SX, SM, NX, NM, C)                                                                                     \
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kPfRequests) : "memory");                                                        \
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");                                                            \
+    pf_request(NX, NM, xr, mr, in_bytes, ld_bytes, t0, p.T, rows_here, k_begin + kPfChunk * ((C) + 2), k_end, wave, lane);     \
+    __builtin_amdgcn_sched_barrier(0);                                                                                         \
+    if (has_rows) pf_multiply(acc, SX, SM, wave, n, h);                                                                        \
+    __builtin_amdgcn_sched_barrier(0);
+    pf_request(s_x0, s_m0, xr, mr, in_bytes, ld_bytes, t0, p.T, rows_here, k_begin, k_end, wave, lane);
+    pf_request(s_x1, s_m1, xr, mr, in_bytes, ld_bytes, t0, p.T, rows_here, k_begin + kPfChunk, k_end, wave, lane);
+    for (int c = 0; c < n_chunks; c += 3) {
+        ADAFUSE_PF_STEP(s_x0, s_m0, s_x2, s_m2, c)
+        if (c + 1 >= n_chunks) break;
+        ADAFUSE_PF_STEP(s_x1, s_m1, s_x0, s_m0, c + 1)
+        if (c + 2 >= n_chunks) break;
+        ADAFUSE_PF_STEP(s_x2, s_m2, s_x1, s_m1, c + 2)
     }
+#undef ADAFUSE_PF_STEP
 
-    // ---- the adapters: for every expert some token of the tile selected, k-steps over the rank.
-    // The experts are dealt to the four waves; a token that did not select the expert contributes a zero operand.
-    const uint64_t present = experts_in_tile(p, t0, 32 * MB, lane);
-    const uint32_t z_bytes = (uint32_t)p.T * (uint32_t)p.k * (uint32_t)p.rp * 2u;
-    const __amdgpu_buffer_rsrc_t zh = make_buffer(p.z_hi, z_bytes), zl = make_buffer(p.z_lo, z_bytes);
-    int turn = 0;
-    for (int e = 0; e < p.E; ++e) {
-        if (!((present >> e) & 1ull)) continue;
-        if ((turn++ & 3) != wave) continue;
-        // B_e's rows of this strip: 2 r bytes per row
-        const __amdgpu_buffer_rsrc_t br = make_buffer(p.b_bank + ((size_t)e * p.out + o0) * p.r, (uint32_t)rows * 2u * (uint32_t)p.r);
-        uint32_t zrow[MB];
+    // ---- the adapters: for every expert some token of the tile selected, k-steps over the rank; a token
+    // that did not select the expert contributes a zero operand.  The experts are dealt to the parts of the
+    // inner dimension (expert e goes to part e % splits: the sum of the parts collects them), so no
+    // workgroup carries all of them behind its share of the base product.
+    // (Operands straight from global memory, one row per lane: a few KB per tile.)
+    const int ow = o0 + 64 * wave;
+    if (p.b_bank != nullptr && has_rows) {
+        // the lane's four tokens: which selection (if any) holds expert e is looked up in registers
+        int sel[4][kMaxTopK];
 #pragma unroll
-        for (int b = 0; b < MB; ++b) {
+        for (int b = 0; b < 4; ++b) {
             const int t = t0 + 32 * b + n;
-            zrow[b] = kOutside;
-            if (t < p.T)
-                for (int j = p.k - 1; j >= 0; --j)  // the FIRST selection of e holds the (folded) result
-                    if (clamp_expert(p.idx[(size_t)t * p.k + j], p.E) == e) zrow[b] = (uint32_t)(t * p.k + j) * (uint32_t)p.rp * 2u;
-        }
-        for (int s = 0; 16 * s < p.rp; ++s) {
-            const int rho = 16 * s + 8 * h;
-            uint4_t bv;
-            if (p.r >= 8) {
-                bv = ld_buffer_b128(br, rho < p.r && o < p.out ? (uint32_t)n * 2u * (uint32_t)p.r + 2u * (uint32_t)rho : kOutside, 0u);
-            } else {  // rank 4: a row is 8 bytes, the upper half of the operand stays zero
-                const uint2_t b2 = ld_buffer_b64(br, rho < p.r && o < p.out ? (uint32_t)n * 8u : kOutside, 0u);
-                bv = uint4_t{b2[0], b2[1], 0u, 0u};
-            }
 #pragma unroll
-            for (int b = 0; b < MB; ++b) {
-                const uint32_t off = rho < p.rp && zrow[b] != kOutside ? zrow[b] + 2u * (uint32_t)rho : kOutside;
-                const uint4_t hv = ld_buffer_b128(zh, off, 0u), lv = ld_buffer_b128(zl, off, 0u);
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(bv), as_operand(lv), acc[b], 0, 0, 0);
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(bv), as_operand(hv), acc[b], 0, 0, 0);
+            for (int j = 0; j < kMaxTopK; ++j) sel[b][j] = t < p.T && j < p.k ? clamp_expert(p.idx[(size_t)t * p.k + j], p.E) : -1;
+        }
+        uint64_t mine = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int j = 0; j < kMaxTopK; ++j)
+                if (sel[b][j] >= 0) mine |= 1ull << sel[b][j];
+        uint64_t present = 0;
+        for (int e = part; e < p.E; e += p.splits)
+            if (__ballot((mine >> e) & 1ull)) present |= 1ull << e;
+        const uint32_t z_bytes = (uint32_t)p.T * (uint32_t)p.k * (uint32_t)p.rp * 2u;
+        const __amdgpu_buffer_rsrc_t zh = make_buffer(p.z_hi, z_bytes), zl = make_buffer(p.z_lo, z_bytes);
+        const int brows = min(64, p.rows - ow);
+        for (int e = part; e < p.E; e += p.splits) {
+            if (!((present >> e) & 1ull)) continue;
+            const __amdgpu_buffer_rsrc_t br = make_buffer(p.b_bank + ((size_t)e * p.rows + ow) * p.r, (uint32_t)brows * 2u * (uint32_t)p.r);
+            uint32_t zrow[4];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                zrow[b] = kOutside;
+#pragma unroll
+                for (int j = kMaxTopK - 1; j >= 0; --j)  // the FIRST selection of e holds the (folded) result
+                    if (sel[b][j] == e) zrow[b] = (uint32_t)((t0 + 32 * b + n) * p.k + j) * (uint32_t)p.rp * 2u;
+            }
+            for (int s = 0; 16 * s < p.rp; ++s) {
+                const int rho = 16 * s + 8 * h;
+                uint4_t bv[2], hv[4], lv[4];
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const int row = 32 * c + n;
+                    if (p.r >= 8) {
+                        bv[c] = ld_buffer_b128(br, rho < p.r && row < brows ? (uint32_t)row * 2u * (uint32_t)p.r + 2u * (uint32_t)rho : kOutside, 0u);
+                    } else {  // rank 4: a row is 8 bytes, the upper half of the operand stays zero
+                        const uint2_t b2 = ld_buffer_b64(br, rho < p.r && row < brows ? (uint32_t)row * 8u : kOutside, 0u);
+                        bv[c] = uint4_t{b2[0], b2[1], 0u, 0u};
+                    }
+                }
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const uint32_t off = rho < p.rp && zrow[b] != kOutside ? zrow[b] + 2u * (uint32_t)rho : kOutside;
+                    hv[b] = ld_buffer_b128(zh, off, 0u);
+                    lv[b] = ld_buffer_b128(zl, off, 0u);
+                }
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+#pragma unroll
+                    for (int c = 0; c < 2; ++c) {
+                        acc[b][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(bv[c]), as_operand(lv[b]), acc[b][c], 0, 0, 0);
+                        acc[b][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(bv[c]), as_operand(hv[b]), acc[b][c], 0, 0, 0);
+                    }
             }
         }
     }
+    if (!has_rows) return;
 
-    reduce_over_waves<MB>(acc, s_part, wave, lane);
-    if (wave != 0) return;
-    // accumulator entries 4 q .. 4 q + 3 of block b: token t0 + 32 b + n, output rows o0 + 8 q + 4 h + 0..3
+    // accumulator entries 4 q .. 4 q + 3 of block (b, c): token t0 + 32 b + n, rows ow + 32 c + 8 q + 4 h + 0..3
+    float *dst0 = p.out + (size_t)part * p.T * p.rows;
 #pragma unroll
-    for (int b = 0; b < MB; ++b) {
+    for (int b = 0; b < 4; ++b) {
         const int t = t0 + 32 * b + n;
         if (t >= p.T) continue;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int oo = o0 + 8 * q + 4 * h;
-            float *dst = p.y + (size_t)t * p.out + oo;
-            if (oo + 3 < p.out && (p.out & 3) == 0) {
-                *reinterpret_cast<float4_t *>(dst) = float4_t{acc[b][4 * q], acc[b][4 * q + 1], acc[b][4 * q + 2], acc[b][4 * q + 3]};
-            } else {
+        for (int c = 0; c < 2; ++c)
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (oo + u < p.out) dst[u] = acc[b][4 * q + u];
+            for (int qq = 0; qq < 4; ++qq) {
+                const int oo = ow + 32 * c + 8 * qq + 4 * h;
+                float *dst = dst0 + (size_t)t * p.rows + oo;
+                if (oo + 3 < p.rows && (p.rows & 3) == 0) {
+                    *reinterpret_cast<float4_t *>(dst) =
+                        float4_t{acc[b][c][4 * qq], acc[b][c][4 * qq + 1], acc[b][c][4 * qq + 2], acc[b][c][4 * qq + 3]};
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (oo + u < p.rows) dst[u] = acc[b][c][4 * qq + u];
+                }
             }
+    }
+}
+
+constexpr int kPfMaxSplits = 32;  // parts of a split inner dimension
+
+// y[i] = parts[0][i] + parts[1][i] + ... in that order, i < n.  All parts are requested before the first
+// addition (a loop of load-then-add would be a chain of memory round trips); unused slots add +0.
+__global__ __launch_bounds__(256) void prefill_sum_kernel(const float *parts, float *y, int64_t n, int splits)
+{
+    const int64_t i = 4 * ((int64_t)blockIdx.x * 256 + threadIdx.x);
+    if (i >= n) return;
+    if (i + 3 < n && (n & 3) == 0) {
+        float4_t v[kPfMaxSplits];
+#pragma unroll
+        for (int q = 0; q < kPfMaxSplits; ++q)
+            v[q] = q < splits ? *reinterpret_cast<const float4_t *>(parts + (size_t)q * n + i) : float4_t{0.f, 0.f, 0.f, 0.f};
+        float4_t s = v[0];
+#pragma unroll
+        for (int q = 1; q < kPfMaxSplits; ++q) s += v[q];
+        *reinterpret_cast<float4_t *>(y + i) = s;
+    } else {
+        for (int64_t j = i; j < n && j < i + 4; ++j) {
+            float s = parts[j];
+            for (int q = 1; q < splits; ++q) s += parts[(size_t)q * n + j];
+            y[j] = s;
         }
     }
+}
+
+// Scaled down-projection of every (token, selection): z = (s * sum of the gates of all selections of
+// that expert by the token) * U[t][e r .. e r + r), U summed over its parts in order, as bf16 hi + lo
+// planes of rp >= r values (zero padded).  A repeated selection of an expert: the first slot takes
+// the folded value, the others zeros.  One thread per (token, selection, rank index).
+struct PrefillGate {
+    const float *u;  // [splits][T][E r]
+    const int32_t *idx;
+    const float *gates;
+    uint16_t *z_hi, *z_lo;
+    int32_t T, E, r, rp, k, splits;
+    float scale;
+};
+
+__global__ __launch_bounds__(256) void prefill_gate_kernel(PrefillGate p)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t total = (int64_t)p.T * p.k * p.rp;
+    if (i >= total) return;
+    const int rho = (int)(i % p.rp);
+    const int j = (int)((i / p.rp) % p.k);
+    const int t = (int)(i / ((int64_t)p.rp * p.k));
+    const int e = clamp_expert(p.idx[(size_t)t * p.k + j], p.E);
+    bool first = true;
+    float c = 0.0f;
+    for (int jj = 0; jj < p.k; ++jj)
+        if (clamp_expert(p.idx[(size_t)t * p.k + jj], p.E) == e) {
+            if (jj < j) first = false;
+            c += p.scale * p.gates[(size_t)t * p.k + jj];
+        }
+    float z = 0.0f;
+    if (first && rho < p.r) {
+        const size_t n = (size_t)p.T * p.E * p.r, at = ((size_t)t * p.E + e) * p.r + rho;
+        float v[kPfMaxSplits];  // all parts requested before the first addition; unused slots add +0
+#pragma unroll
+        for (int q = 0; q < kPfMaxSplits; ++q) v[q] = q < p.splits ? p.u[(size_t)q * n + at] : 0.0f;
+        float u = v[0];
+#pragma unroll
+        for (int q = 1; q < kPfMaxSplits; ++q) u += v[q];
+        z = c * u;
+    }
+    const uint32_t hi = pack_bf16_rne(z, 0.0f) & 0xffffu;
+    const uint32_t lo = pack_bf16_rne(z - bf16_lo(hi), 0.0f) & 0xffffu;
+    p.z_hi[i] = (uint16_t)hi;
+    p.z_lo[i] = (uint16_t)lo;
 }
 
 }  // namespace adafuse
