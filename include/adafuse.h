@@ -138,8 +138,9 @@ typedef enum {
     ADAFUSE_OPT_GEMM_WAVES = 1, /* waves per workgroup of ADAFUSE_KERNEL_GEMM (tile 64 x 64 waves): 4, 8, or 0 =
                                    chosen from the matrices' row pitches */
     ADAFUSE_OPT_GEMM_FORM = 2,  /* form of ADAFUSE_KERNEL_GEMM: 0 = by the length of the contraction, 1 = unrolled,
-                                   3 = overlapped with the W fetch, 4 = 128-row tiles that share the column
-                                   operands between two halves; each wherever that form can take the launch */
+                                   3 = overlapped with the W fetch, 4 = chains of eight vertically adjacent tiles
+                                   per workgroup (column operands resident, next tile's W in flight during the
+                                   contraction); each wherever that form can take the launch */
     ADAFUSE_OPT_XCD_RUN = 3,    /* tile order: 0 = plain, 1 = one contiguous eighth of the tile list per XCD
                                    (default), G > 1 = runs of G tiles per XCD */
     ADAFUSE_OPT_PANEL_KB = 4,   /* column-operand budget of a column panel in KiB (default 2048) */

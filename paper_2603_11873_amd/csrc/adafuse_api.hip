@@ -15,7 +15,7 @@
 #include "pregate.hpp"
 #include "switch_gemm.hpp"
 #include "switch_gemm_overlap.hpp"
-#include "switch_gemm_tall.hpp"
+#include "switch_gemm_strip.hpp"
 #include "switch_mfma.hpp"
 #include "switch_valu.hpp"
 
@@ -44,7 +44,7 @@ struct adafuse_ctx {
     float *scratch = nullptr;            // this device's copy of the file-scope scratch array
     MatDev *d_mats = nullptr;
     TileDev *d_tiles = nullptr;          // [0, n_tiles): whole model; [n_tiles, 2 n_tiles): matrix by matrix
-    TileDev *d_tall = nullptr;           // the whole model in tiles of 128 rows (the tall form of the rank-looped kernel), or null
+    TileDev *d_tall = nullptr;           // the whole model in chains of kStripTiles vertically adjacent tiles (the strip form of the rank-looped kernel), or null
     int64_t n_tall = 0;
     std::vector<int64_t> mat_tile_off;   // per-matrix ranges inside the second section (n_mats + 1 entries)
 };
@@ -127,20 +127,18 @@ bool launch_mfma_any(const SwitchParams &p, int nt, int64_t n_tiles, hipStream_t
 // 7 k-steps of 16 rank indices per tile, the overlapped one (W straight into LDS,
 // contraction meanwhile) from 8 on.  ADAFUSE_OPT_GEMM_FORM forces one: 1 = the unrolled
 // form wherever it can take the launch, 3 = the overlapped form for short contractions too.
-enum GemmForm { kFormUnrolled, kFormOverlap, kFormTall };
+enum GemmForm { kFormUnrolled, kFormOverlap, kFormStrip };
 
 constexpr bool can_unroll(int r, int nt) { return nt <= 2 || (nt == 4 && r <= 16); }  // every row operand fits beside the W tile
 constexpr bool can_overlap(int r, int nt) { return nt * ((r + 15) / 16) <= 64; }
-constexpr bool can_tall(int r, int nt) { return nt * ((r + 15) / 16) == 8 || nt * ((r + 15) / 16) == 16; }
+constexpr bool can_strip(int r, int nt) { return nt * ((r + 15) / 16) == 8 || nt * ((r + 15) / 16) == 16; }
 
-// forced: ADAFUSE_OPT_GEMM_FORM (0 = by the length of the contraction); tall_ok: the context holds the
-// table of 128-row tiles (4-wave workgroups, whole-model launch).  The 128-row form is only run on
-// request: it halves the column-operand bytes per W byte, but with two workgroups per CU instead of
-// three it measured no faster (rank 128 top-2: 6390 against 6290 us; rank 64: 4800 against 4510 us).
-GemmForm pick_gemm_form(int r, int nt, int forced, bool tall_ok)
+// forced: ADAFUSE_OPT_GEMM_FORM (0 = by the length of the contraction); strip_ok: the context holds the
+// table of tile chains (4-wave workgroups, whole-model launch).
+GemmForm pick_gemm_form(int r, int nt, int forced, bool strip_ok)
 {
     const int steps = nt * ((r + 15) / 16);
-    if (forced == 4 && tall_ok && can_tall(r, nt)) return kFormTall;
+    if (forced == 4 && strip_ok && can_strip(r, nt)) return kFormStrip;
     if (!can_unroll(r, nt)) return kFormOverlap;
     if (!can_overlap(r, nt)) return kFormUnrolled;
     if (forced == 1) return kFormUnrolled;
@@ -154,9 +152,9 @@ bool launch_gemm_form(const SwitchParams &p, GemmForm form, int64_t n_tiles, hip
     static_assert(can_unroll(R, NT) || can_overlap(R, NT), "some form takes every (rank, terms)");
     const dim3 grid((unsigned)n_tiles), block(64 * NW);
     switch (form) {
-    case kFormTall:
-        if constexpr (can_tall(R, NT) && NW == 4) {
-            hipLaunchKernelGGL((switch_gemm_tall_kernel<R, NT>), grid, block, 0, s, p);
+    case kFormStrip:
+        if constexpr (can_strip(R, NT) && NW == 4) {
+            hipLaunchKernelGGL((switch_gemm_strip_kernel<R, NT>), grid, block, 0, s, p);
             return true;
         }
         break;
@@ -306,9 +304,9 @@ adafuse_status build_tables(adafuse_ctx *c, int32_t kernel)
     host::Tables t, tall;
     if (!host::build_tile_tables(c->mats, plan, t)) return ADAFUSE_ERR_SHAPE;
     const bool want_tall = kernel == ADAFUSE_KERNEL_GEMM && gemm_waves == 4;
-    if (want_tall) {  // the same walk in tiles of 128 rows
+    if (want_tall) {  // the same walk in chains of kStripTiles tiles
         host::TablePlan tp = plan;
-        tp.tile_rows = kTallTileRows;
+        tp.tile_rows = kStripRows;
         if (!host::build_tile_tables(c->mats, tp, tall)) return ADAFUSE_ERR_SHAPE;
     }
 
@@ -533,7 +531,7 @@ adafuse_status switch_launches(adafuse_ctx *ctx, const int32_t *idx_prev, const 
             // nothing to overlap, and W first, through registers, is the faster copy
             const int nt = terms_bucket(n_terms > 0 ? n_terms : 1);
             GemmForm form = copy_only ? kFormUnrolled : pick_gemm_form(ctx->r, nt, ctx->opt_form, !per_matrix && ctx->d_tall != nullptr);
-            if (form == kFormTall) {  // its own table: the whole model in tiles of 128 rows
+            if (form == kFormStrip) {  // its own table: the whole model in chains of vertically adjacent tiles
                 p.tiles = ctx->d_tall;
                 if (!launch_gemm(p, nt, 4, form, ctx->n_tall, s)) return ADAFUSE_ERR_ARG;
             } else if (!launch_gemm(p, nt, ctx->gemm_waves, form, count, s)) {
@@ -755,7 +753,7 @@ const char *adafuse_switch_kernel_name(const adafuse_ctx *ctx, int32_t k, int32_
     case ADAFUSE_KERNEL_GEMM:
         if (copy_only) return "switch_gemm_kernel";
         switch (pick_gemm_form(ctx->r, terms_bucket(n_terms), ctx->opt_form, ctx->d_tall != nullptr)) {
-        case kFormTall: return "switch_gemm_tall_kernel";
+        case kFormStrip: return "switch_gemm_strip_kernel";
         case kFormOverlap: return "switch_gemm_overlap_kernel";
         default: return "switch_gemm_kernel";
         }

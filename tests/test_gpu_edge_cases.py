@@ -88,10 +88,10 @@ def test_nothing_outside_the_selected_slices_reaches_the_update(oracle, kernel, 
 
 
 @pytest.mark.parametrize("r", [4, 8, 16])
-@pytest.mark.parametrize("form,name", [(4, "switch_gemm_tall_kernel"), (0, "switch_gemm_overlap_kernel")])
+@pytest.mark.parametrize("form,name", [(4, "switch_gemm_strip_kernel"), (0, "switch_gemm_overlap_kernel")])
 def test_padded_ranks_in_the_eight_term_form(oracle, r, form, name):
     """In place with top-4: a SWAP carries eight terms, which the default kernel runs in its
-    64-row overlapped form and, on request, in its 128-row form (both fetch the operands 16 bytes
+    one-tile overlapped form and, on request, in its chained form (both fetch the operands 16 bytes
     per lane, with the rank padding through the descriptor).  Previous and next token share the
     bank's last expert; three experts in between are poison."""
     g = torch.Generator().manual_seed(7 + r)

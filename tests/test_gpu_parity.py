@@ -631,11 +631,11 @@ def test_per_matrix_launches_give_the_same_bits(oracle):
 @pytest.mark.parametrize("form", [0, 4])
 def test_rank_looped_kernel_modes(oracle, r, k, inplace, form):
     """The rank-looped kernels in all forms -- unrolled (up to 7 k-steps of 16 rank indices per
-    tile), the 128-row form that shares the column operands between two halves (8 and 16 k-steps:
-    e.g. top-2 at ranks 64 and 128; run with form = 4) and the 64-row form overlapped with the W
+    tile), the chained form that keeps the column operands resident over eight vertically adjacent
+    tiles (8 and 16 k-steps: e.g. top-2 at ranks 64 and 128; run with form = 4) and the one-tile form overlapped with the W
     fetch (the library's choice from 8 k-steps on, up to 64 in phases of 16: 4 terms at rank 128, 8 terms at any rank,
     the zero-padded rank 8 included; also with terms left unused: k = 3): MERGE / SWAP / UNMERGE,
-    out of place and in place, two ragged matrices (190 rows: one full 128-row tile and a ragged one)."""
+    out of place and in place, two ragged matrices (190 rows: a chain that ends after three tiles, the last one ragged)."""
     dev = torch.device("cuda:0")
     g = torch.Generator().manual_seed(r * 10 + k)
     E = 4
@@ -701,7 +701,7 @@ def test_rank_looped_kernel_modes(oracle, r, k, inplace, form):
 def test_switch_kernel_name_follows_the_dispatch(r, k, inplace, mode, expect):
     """The label measurements use for a launch is the form the library would run: by the
     number of k-steps of 16 rank indices per tile (terms rounded up to 1, 2, 4 or 8): unrolled up
-    to 7, overlapped with the W fetch from 8 on; the 128-row form on request at 8 and 16."""
+    to 7, overlapped with the W fetch from 8 on; the chained form on request at 8 and 16."""
     dev = torch.device("cuda:0")
     wb = torch.zeros((64, 256), dtype=torch.bfloat16, device=dev)
     a = torch.zeros((4, r, 256), dtype=torch.bfloat16, device=dev)
@@ -713,8 +713,8 @@ def test_switch_kernel_name_follows_the_dispatch(r, k, inplace, mode, expect):
     steps = (2 * k if inplace and mode == "SWAP" else k)
     steps = (1 if steps <= 1 else 2 if steps <= 2 else 4 if steps <= 4 else 8) * ((r + 15) // 16)
     if mode != "UNMERGE" or inplace:
-        ctx.set_option(af.OPT_GEMM_FORM, 4)       # the 128-row form, where it exists: 8 or 16 k-steps
-        assert ctx.switch_kernel_name(k, getattr(af, mode)) == ("switch_gemm_tall_kernel" if steps in (8, 16) else expect)
+        ctx.set_option(af.OPT_GEMM_FORM, 4)       # the chained form, where it exists: 8 or 16 k-steps
+        assert ctx.switch_kernel_name(k, getattr(af, mode)) == ("switch_gemm_strip_kernel" if steps in (8, 16) else expect)
     ctx.set_kernel(af.KERNEL_VALU)
     assert ctx.switch_kernel_name(k, af.SWAP) == "switch_valu_kernel"
     ctx.close()
