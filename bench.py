@@ -32,7 +32,7 @@ def parse_args():
     ap.add_argument("--workload", default="llama2_7b_all")
     ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma", "gemm"])
     ap.add_argument("--gemm-form", type=int, default=0, choices=[0, 1, 3, 4],
-                    help="ADAFUSE_OPT_GEMM_FORM: 0 library's choice, 1 unrolled, 3 overlapped (64-row tiles), 4 128-row tiles")
+                    help="ADAFUSE_OPT_GEMM_FORM: 0 library's choice, 1 unrolled, 3 overlapped, 4 chained (eight vertically adjacent tiles per workgroup)")
     ap.add_argument("--gemm-waves", type=int, default=0, choices=[0, 4, 8], help="ADAFUSE_OPT_GEMM_WAVES (0: library's choice)")
     ap.add_argument("--mode", default="swap", choices=["swap", "unmerge"],
                     help="unmerge times the plain W_base->W_work copy over the same tile table")
