@@ -351,12 +351,20 @@ def main():
         with torch.cuda.stream(stream):
             cp = timed_launches(torch, stream, lambda: ctx.fused_switch(None, None, None, None, wl.k, wl.scale,
                                                                         af.UNMERGE, stream=stream), 16)
+            # ... and each direction alone over the same tiles: W_base read and discarded, W_work zeroed
+            rd = timed_launches(torch, stream, lambda: ctx.hbm_probe(af.PROBE_READ_BASE, stream=stream), 16)
+            wr = timed_launches(torch, stream, lambda: ctx.hbm_probe(af.PROBE_ZERO_WORK, stream=stream), 16)
             last = (args.warmup + args.steps - 1) % T   # leave W_work as the timed loop left it
             ctx.fused_switch(None, None, idx[last], gates[last], wl.k, wl.scale, af.MERGE, stream=stream)
             torch.cuda.synchronize()
         copy_gbs = 4 * wl.elements / (cp["mean"] * 1e-6) / 1e9
+        read_gbs, write_gbs = (2 * wl.elements / (x["mean"] * 1e-6) / 1e9 for x in (rd, wr))
+        serial_gbs = 2.0 / (1.0 / read_gbs + 1.0 / write_gbs)
         out["roofline"]["copy_kernel"] = {"us": cp["mean"], "GB/s": copy_gbs, "frac_of_peak": copy_gbs / HBM_PEAK_GBS,
                                           "switch_vs_copy": achieved / copy_gbs}
+        # what the chip gives one direction at a time, and a pass that did N bytes of each back to back
+        out["roofline"]["one_direction"] = {"read_only_GB/s": read_gbs, "write_only_GB/s": write_gbs,
+                                            "read_then_write_GB/s": serial_gbs, "switch_vs_read_then_write": achieved / serial_gbs}
     if not args.no_cpu_baseline:
         t = (args.warmup + args.steps - 1) % T
         out["cpu_baseline"] = cpu_baseline(wl, mats, hidden, router, t, min(args.cpu_layers, wl.layers))

@@ -164,6 +164,21 @@ adafuse_status adafuse_get_info(const adafuse_ctx *ctx, adafuse_info *info);
 const char *adafuse_switch_kernel_name(const adafuse_ctx *ctx, int32_t k, int32_t mode);
 
 /*
+ * Measurement aid (not a step of the method): one pass in ONE direction over the
+ * same tile table the fused switch walks, one workgroup per tile, 16 bytes per
+ * lane.  The two rates bracket what the switch's read-plus-write pass can reach
+ * on the device at hand.
+ *   ADAFUSE_PROBE_READ_BASE  reads every element of every w_base and discards it
+ *   ADAFUSE_PROBE_ZERO_WORK  writes zero bits to every element of every w_work:
+ *                            the merged weights are gone, merge again before use;
+ *                            ERR_ARG for an in-place context (w_work == w_base)
+ * Enqueues one kernel on `hip_stream`; no allocation, no synchronisation.
+ * ERR_ARG for an unknown direction or a tile shape the aid is not built for.
+ */
+typedef enum { ADAFUSE_PROBE_READ_BASE = 0, ADAFUSE_PROBE_ZERO_WORK = 1 } adafuse_probe_direction;
+adafuse_status adafuse_hbm_probe(adafuse_ctx *ctx, int32_t direction, void *hip_stream);
+
+/*
  * Pre-gating router for T tokens (Eq.1's G applied to x^1, Eq.2):
  *   logits[t][e] = sum_i hidden[t][i] * w_router[e][i]      (fp32 result)
  *   idx[t][0..k)  = the k largest logits of token t, ordered by (logit

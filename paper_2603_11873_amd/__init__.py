@@ -19,6 +19,8 @@ from .binding import (  # noqa: F401
     OPT_MFMA_SHAPE,
     OPT_PANEL_KB,
     OPT_XCD_RUN,
+    PROBE_READ_BASE,
+    PROBE_ZERO_WORK,
     SWAP,
     UNMERGE,
     AdafuseError,

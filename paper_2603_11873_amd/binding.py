@@ -10,10 +10,11 @@ MERGE, UNMERGE, SWAP = 0, 1, 2
 GATE_SOFTMAX_OVER_TOPK, GATE_TOPK_OF_SOFTMAX = 0, 1
 KERNEL_AUTO, KERNEL_VALU, KERNEL_MFMA, KERNEL_GEMM = 0, 1, 2, 3
 OPT_KERNEL, OPT_GEMM_WAVES, OPT_GEMM_FORM, OPT_XCD_RUN, OPT_PANEL_KB, OPT_MFMA_SHAPE = range(6)
+PROBE_READ_BASE, PROBE_ZERO_WORK = 0, 1
 
 EXPORTS = ["adafuse_create", "adafuse_destroy", "adafuse_set_option", "adafuse_get_info",
            "adafuse_pregate", "adafuse_fused_switch", "adafuse_switch_per_matrix", "adafuse_forward_merged", "adafuse_forward_dynamic",
-           "adafuse_forward_dynamic_static", "adafuse_prefill", "adafuse_prefill_workspace_bytes", "adafuse_switch_kernel_name", "adafuse_status_string"]
+           "adafuse_forward_dynamic_static", "adafuse_prefill", "adafuse_prefill_workspace_bytes", "adafuse_hbm_probe", "adafuse_switch_kernel_name", "adafuse_status_string"]
 
 
 class AdafuseError(RuntimeError):
@@ -74,6 +75,8 @@ def load_library():
     L.adafuse_prefill.argtypes = [vp, i32, vp, i32, vp, vp, i32, f32, vp, vp, C.c_size_t, vp]
     L.adafuse_prefill_workspace_bytes.restype = i32
     L.adafuse_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_size_t)]
+    L.adafuse_hbm_probe.restype = i32
+    L.adafuse_hbm_probe.argtypes = [vp, i32, vp]
     L.adafuse_switch_kernel_name.restype = C.c_char_p
     L.adafuse_switch_kernel_name.argtypes = [vp, i32, i32]
     L.adafuse_status_string.restype = C.c_char_p
@@ -170,6 +173,12 @@ class Context:
         """adafuse_switch_kernel_name: the device function a switch with these arguments launches, or None."""
         name = load_library().adafuse_switch_kernel_name(self._h, k, mode)
         return None if name is None else name.decode()
+
+    def hbm_probe(self, direction, stream=None):
+        """adafuse_hbm_probe: PROBE_READ_BASE reads every w_base tile, PROBE_ZERO_WORK zeroes every w_work tile."""
+        st = load_library().adafuse_hbm_probe(self._h, direction, _stream_handle(stream))
+        if st != 0:
+            raise AdafuseError(st, "adafuse_hbm_probe")
 
     def fused_switch(self, idx_prev, gates_prev, idx_next, gates_next, k, scale, mode, stream=None):
         """adafuse_fused_switch; idx/gates are device tensors (int32[k] / fp32[k]) or None."""

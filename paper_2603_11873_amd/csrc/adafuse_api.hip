@@ -6,11 +6,13 @@
 
 #include <algorithm>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include "device_types.hpp"
 #include "host_tables.hpp"
 #include "forward.hpp"
+#include "hbm_probe.hpp"
 #include "prefill.hpp"
 #include "pregate.hpp"
 #include "switch_gemm.hpp"
@@ -27,7 +29,8 @@ using namespace adafuse;
 // address is looked up once per context (build_tables, with the context's device current) and
 // kept in adafuse_ctx::scratch, which is what the launches pass.
 constexpr int kScratchFloats = 1024;  // k * r <= 8 * 128
-static __device__ __align__(256) float scratch[kScratchFloats];
+constexpr int kSinkFloats = 64;       // behind z: the word the read probe keeps its loads alive with
+static __device__ __align__(256) float scratch[kScratchFloats + kSinkFloats];
 
 struct adafuse_ctx {
     std::vector<adafuse_matrix_desc> mats;
@@ -735,6 +738,35 @@ adafuse_status adafuse_prefill(adafuse_ctx *ctx, int32_t mat, const void *x, int
     if (pl.up.splits > 1) {
         const int64_t n_y = (int64_t)T * m.out;
         hipLaunchKernelGGL(prefill_sum_kernel, dim3((unsigned)((n_y + 1023) / 1024)), dim3(256), 0, s, parts, y, n_y, pl.up.splits);
+    }
+    return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
+}
+
+adafuse_status adafuse_hbm_probe(adafuse_ctx *ctx, int32_t direction, void *hip_stream)
+{
+    if (!ctx) return ADAFUSE_ERR_NULL;
+    if (direction != ADAFUSE_PROBE_READ_BASE && direction != ADAFUSE_PROBE_ZERO_WORK) return ADAFUSE_ERR_ARG;
+    if (ctx->inplace && direction == ADAFUSE_PROBE_ZERO_WORK) return ADAFUSE_ERR_ARG;  // would erase the only copy of W
+    if (!on_ctx_device(ctx)) return ADAFUSE_ERR_ARG;
+    if (ctx->n_tiles == 0) return ADAFUSE_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int pieces = ctx->tile_rows * ctx->tile_cols / 8;
+    uint32_t *sink = reinterpret_cast<uint32_t *>(ctx->scratch + kScratchFloats);
+    const dim3 grid((unsigned)ctx->n_tiles), block(256);
+    auto launch = [&](auto pt) {
+        constexpr int PT = decltype(pt)::value;
+        if (direction == ADAFUSE_PROBE_ZERO_WORK)
+            hipLaunchKernelGGL((hbm_probe_kernel<PT, true>), grid, block, 0, s, ctx->d_tiles, ctx->tile_cols, sink);
+        else
+            hipLaunchKernelGGL((hbm_probe_kernel<PT, false>), grid, block, 0, s, ctx->d_tiles, ctx->tile_cols, sink);
+    };
+    if (pieces % 256 != 0) return ADAFUSE_ERR_ARG;
+    switch (pieces / 256) {
+    case 4: launch(std::integral_constant<int, 4>{}); break;
+    case 8: launch(std::integral_constant<int, 8>{}); break;
+    case 16: launch(std::integral_constant<int, 16>{}); break;
+    case 32: launch(std::integral_constant<int, 32>{}); break;
+    default: return ADAFUSE_ERR_ARG;  // a tile shape this aid is not built for
     }
     return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
 }

@@ -193,3 +193,42 @@ def test_inplace_swap_with_a_shared_expert_one_step_apart(oracle, r):
     tally.add(compare_inplace(oracle, before, wlmod.bits(a), wlmod.bits(b), got, prev, nxt, 2.0), ULP_TOL)
     tally.finish(1e-4)
     ctx.close()
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_one_direction_probes_touch_exactly_their_side(kernel):
+    """adafuse_hbm_probe: the read pass changes nothing; the write pass zeroes every element of
+    W_work inside the matrix and nothing outside it (padding columns, the allocation's tail), and
+    is refused where W_work is the only copy of the weights."""
+    g = torch.Generator().manual_seed(77)
+    out, in_, ldw, E, r = 190, 264, 272, 3, 8
+    base = (0.02 * torch.randn((out, ldw), generator=g)).to(torch.bfloat16).cuda()
+    a = (in_ ** -0.5 * torch.randn((E, r, in_), generator=g)).to(torch.bfloat16).cuda()
+    b = (0.05 * torch.randn((E, out, r), generator=g)).to(torch.bfloat16).cuda()
+    work_full, work_big = _guarded(torch.ones((out, ldw), dtype=torch.bfloat16))
+    work_full.view(torch.int16).fill_(NAN_BITS)
+    before_base = base.clone()
+    ctx = af.Context([(base[:, :in_], work_full[:, :in_], a, b)], 2)
+    ctx.set_kernel(kernel)
+    ctx.hbm_probe(af.PROBE_READ_BASE)
+    _sync()
+    assert torch.equal(base.view(torch.int16), before_base.view(torch.int16))
+    assert bool((work_full.view(torch.int16) == NAN_BITS).all())
+    ctx.hbm_probe(af.PROBE_ZERO_WORK)
+    _sync()
+    assert bool((work_full[:, :in_].view(torch.int16) == 0).all())
+    assert bool((work_full[:, in_:].view(torch.int16) == NAN_BITS).all())
+    tail = work_big[out * ldw:].view(torch.int16)
+    assert bool(((tail == NAN_BITS) | (tail == INF_BITS)).all())
+    assert torch.equal(base.view(torch.int16), before_base.view(torch.int16))
+    with pytest.raises(af.AdafuseError):
+        ctx.hbm_probe(2)
+    ctx.close()
+    w = base[:, :in_]
+    inplace = af.Context([(w, w, a, b)], 2)
+    inplace.hbm_probe(af.PROBE_READ_BASE)
+    with pytest.raises(af.AdafuseError):
+        inplace.hbm_probe(af.PROBE_ZERO_WORK)
+    _sync()
+    assert torch.equal(base.view(torch.int16), before_base.view(torch.int16))
+    inplace.close()
