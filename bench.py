@@ -128,18 +128,26 @@ def forward_context(torch, af, ctx, wl, mats, idx, gates, stream, reps=20):
 
 
 def prefill_bench(torch, af, ctx, wl, mats, hidden, router, T, stream, reps):
-    """T tokens through every matrix (one adafuse_prefill call per matrix: two launches each)."""
+    """T tokens through every matrix: one adafuse_prefill_group call per set of matrices of a layer that take
+    the same input (q, k, v / o / gate, up / down -- the dependency structure of a Llama layer)."""
     dev = mats[0][0].device
     reps_h = (T + wl.T - 1) // wl.T
     h = hidden.repeat(reps_h, 1)[:T].contiguous()
     idx, gates, _ = af.pregate(h, router, wl.k, stream=stream)
+    per_layer = len(wl.mats)
+    names = [m[0] for m in wl.mats]
+    sets = [[names.index(n) for n in grp if n in names] for grp in (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))]
+    sets = [g for g in sets if g]
+    assert sorted(i for g in sets for i in g) == list(range(per_layer))
+    groups = [[layer * per_layer + i for i in g] for layer in range(wl.layers) for g in sets]
     xs = {i: torch.randn((T, i), device=dev).to(torch.bfloat16) for i in {m[0].shape[1] for m in mats}}
-    ys = {o: torch.empty((T, o), dtype=torch.float32, device=dev) for o in {m[0].shape[0] for m in mats}}
-    ws = torch.empty(max(ctx.prefill_workspace_bytes(mi, T, wl.k) for mi in range(len(mats))), dtype=torch.uint8, device=dev)
+    ys = {mi: torch.empty((T, mats[mi][0].shape[0]), dtype=torch.float32, device=dev) for mi in range(per_layer)}
+    ws = torch.empty(max(ctx.prefill_group_workspace_bytes(g, T, wl.k) for g in groups[:len(sets)]), dtype=torch.uint8, device=dev)
 
     def run():
-        for mi, m in enumerate(mats):
-            ctx.prefill(mi, xs[m[0].shape[1]], idx, gates, wl.scale, y=ys[m[0].shape[0]], workspace=ws, stream=stream)
+        for g in groups:
+            ctx.prefill_group(g, xs[mats[g[0]][0].shape[1]], idx, gates, wl.scale, ys=[ys[mi % per_layer] for mi in g],
+                              workspace=ws, stream=stream)
 
     with torch.cuda.stream(stream):
         t = timed_launches(torch, stream, run, reps, warm=2)
@@ -150,17 +158,22 @@ def prefill_bench(torch, af, ctx, wl, mats, hidden, router, T, stream, reps):
     hbm = (w_bytes + io_bytes) / sec / 1e9
     tf = flops / sec / 1e12
     bound = "hbm" if T * 2 < 2 * MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS else "mfma"   # flops per W byte = T
+    few = T <= 512
     return {
         "metric": "prefill latency, all adapted matrices, un-merged adapters with per-token decisions (us)",
         "value": t["mean"], "unit": "us", "n_gpus": 1, "steps": reps, "warmup": 2, "ms_per_step": t["mean"] * 1e-3,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "tokens": T, "matrices": wl.n_mats, "E": wl.E, "r": wl.r, "k": wl.k,
-                   "launches": "3 or 4 per matrix", "step": "adafuse_prefill on every matrix, one stream"},
+                   "calls": len(groups), "groups_per_layer": [[names[i] for i in g] for g in sets],
+                   "launches": "2 per group" if few else "3 or 4 per matrix",
+                   "step": "adafuse_prefill_group on every set of matrices that share an input, one stream"},
         "roofline": {"bound": bound,
                      "achieved": hbm if bound == "hbm" else tf, "peak": HBM_PEAK_GBS if bound == "hbm" else MFMA_BF16_PEAK_TFLOPS,
                      "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
                      "frac": hbm / HBM_PEAK_GBS if bound == "hbm" else tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                     "kernel": "prefill_gemm_kernel (bank and base passes) + prefill_gate_kernel + prefill_sum_kernel", "hbm_GBs": hbm, "mfma_TFLOPs": tf,
+                     "kernel": ("prefill_gemm_kernel (base and bank products of a group in one launch) + prefill_finish_kernel" if few else
+                                "prefill_gemm_kernel (bank and base passes) + prefill_gate_kernel + prefill_sum_kernel"),
+                     "hbm_GBs": hbm, "mfma_TFLOPs": tf,
                      "algorithmic_bytes": w_bytes + io_bytes, "algorithmic_flops": flops, "median_us": t["median"]},
     }
 

@@ -288,17 +288,20 @@ adafuse_status adafuse_forward_dynamic(adafuse_ctx *ctx, const int32_t *idx, con
  * y        DEVICE fp32 [T][out], contiguous, 16-byte aligned; every element is written once
  *          (no accumulation into previous contents, no atomics: the same bits on every run)
  * workspace  DEVICE, 16-byte aligned, at least adafuse_prefill_workspace_bytes() bytes
- *          (workspace_bytes is checked): the scaled down-projections s g A x of every (token,
- *          selection) as two bf16 planes (value and rounding remainder, 16 significant bits),
- *          and the fp32 parts of the products whose inner dimension is split across
- *          workgroups (few tokens leave too few tiles to fill the chip).  Owned by the caller;
- *          its previous contents do not matter and nothing in it needs clearing.
+ *          (workspace_bytes is checked): the fp32 parts of the products whose inner dimension
+ *          is split across workgroups (few tokens leave too few tiles to fill the chip) and,
+ *          with more than 512 tokens, the scaled down-projections s g A x of every (token,
+ *          selection) as two bf16 planes (value and rounding remainder, 16 significant bits).
+ *          Owned by the caller; its previous contents do not matter and nothing in it needs
+ *          clearing.
  * Arithmetic: bf16 operands on the matrix cores, fp32 accumulation; the parts of a split inner
  * dimension are added in a fixed order: the same bits on every run.
- * Three or four launches on `hip_stream` (down projection over the whole bank, gating, base
- * product with the up projection as further inner dimension, sum of the parts), no
- * allocation, no synchronisation.  Needs an out-of-place context (the base weights must be
- * unmodified).
+ * Launches on `hip_stream`, no allocation, no synchronisation.  Up to 512 tokens: two (the
+ * base product and the down-projection through the whole bank share one, cut into the same
+ * number of parts; the second sums the parts and adds the up-projections in fp32).  More
+ * tokens: three or four (down projection over the whole bank, gating, base product with the
+ * up projection as further inner dimension, sum of the parts).  Needs an out-of-place context
+ * (the base weights must be unmodified).
  * Errors: NULL pointer -> ERR_NULL; mat, T < 0, k out of range, in-place context, workspace
  * too small, wrong device -> ERR_ARG; misaligned x / y / workspace -> ERR_ALIGN;
  * T * in or T * k * r beyond 2^30 elements -> ERR_SHAPE.  T == 0 is a no-op.
@@ -311,6 +314,26 @@ adafuse_status adafuse_prefill(adafuse_ctx *ctx, int32_t mat, const void *x, int
  * `mat` (HOST result in *bytes; 0 for T == 0).  Errors as adafuse_prefill's argument checks. */
 adafuse_status adafuse_prefill_workspace_bytes(const adafuse_ctx *ctx, int32_t mat, int32_t T, int32_t k,
                                                size_t *bytes);
+
+/*
+ * adafuse_prefill for a GROUP of matrices that take the same input (the q, k and v projections
+ * of a layer; gate and up): the same results, y[i] = adafuse_prefill(mats[i]) up to the order
+ * of the fp32 sums, with the launches shared.  The method's own argument for one batched
+ * launch ("SGMM Kernel": many small launches leave the GPU under-used) holds here as well: at a
+ * hundred tokens a launch costs more than streaming a 4096 x 4096 matrix once.  Up to 512
+ * tokens the whole group takes two launches; with more tokens the matrices run one after the
+ * other as in adafuse_prefill.
+ * mats     HOST int32 [n], distinct matrix indices, 1 <= n <= 4, all with the same `in`
+ *          (else ERR_SHAPE)
+ * y        HOST array of n DEVICE pointers: y[i] fp32 [T][out of mats[i]], 16-byte aligned
+ * workspace  at least adafuse_prefill_group_workspace_bytes() bytes
+ * Everything else as adafuse_prefill.
+ */
+adafuse_status adafuse_prefill_group(adafuse_ctx *ctx, const int32_t *mats, int32_t n, const void *x, int32_t T,
+                                     const int32_t *idx, const float *gates, int32_t k, float scale,
+                                     float *const *y, void *workspace, size_t workspace_bytes, void *hip_stream);
+adafuse_status adafuse_prefill_group_workspace_bytes(const adafuse_ctx *ctx, const int32_t *mats, int32_t n,
+                                                     int32_t T, int32_t k, size_t *bytes);
 
 /*
  * adafuse_forward_dynamic for callers that cannot allocate device memory or hand over a

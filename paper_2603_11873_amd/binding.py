@@ -14,7 +14,7 @@ PROBE_READ_BASE, PROBE_ZERO_WORK = 0, 1
 
 EXPORTS = ["adafuse_create", "adafuse_destroy", "adafuse_set_option", "adafuse_get_info",
            "adafuse_pregate", "adafuse_fused_switch", "adafuse_switch_per_matrix", "adafuse_forward_merged", "adafuse_forward_dynamic",
-           "adafuse_forward_dynamic_static", "adafuse_prefill", "adafuse_prefill_workspace_bytes", "adafuse_hbm_probe", "adafuse_switch_kernel_name", "adafuse_status_string"]
+           "adafuse_forward_dynamic_static", "adafuse_prefill", "adafuse_prefill_workspace_bytes", "adafuse_prefill_group", "adafuse_prefill_group_workspace_bytes", "adafuse_hbm_probe", "adafuse_switch_kernel_name", "adafuse_status_string"]
 
 
 class AdafuseError(RuntimeError):
@@ -75,6 +75,10 @@ def load_library():
     L.adafuse_prefill.argtypes = [vp, i32, vp, i32, vp, vp, i32, f32, vp, vp, C.c_size_t, vp]
     L.adafuse_prefill_workspace_bytes.restype = i32
     L.adafuse_prefill_workspace_bytes.argtypes = [vp, i32, i32, i32, C.POINTER(C.c_size_t)]
+    L.adafuse_prefill_group.restype = i32
+    L.adafuse_prefill_group.argtypes = [vp, C.POINTER(i32), i32, vp, i32, vp, vp, i32, f32, C.POINTER(vp), vp, C.c_size_t, vp]
+    L.adafuse_prefill_group_workspace_bytes.restype = i32
+    L.adafuse_prefill_group_workspace_bytes.argtypes = [vp, C.POINTER(i32), i32, i32, i32, C.POINTER(C.c_size_t)]
     L.adafuse_hbm_probe.restype = i32
     L.adafuse_hbm_probe.argtypes = [vp, i32, vp]
     L.adafuse_switch_kernel_name.restype = C.c_char_p
@@ -245,6 +249,36 @@ class Context:
         if st != 0:
             raise AdafuseError(st, "adafuse_prefill")
         return y
+
+    def prefill_group_workspace_bytes(self, mats, T, k):
+        """adafuse_prefill_group_workspace_bytes"""
+        n = C.c_size_t(0)
+        arr = (C.c_int32 * len(mats))(*mats)
+        st = load_library().adafuse_prefill_group_workspace_bytes(self._h, arr, len(mats), T, k, C.byref(n))
+        if st != 0:
+            raise AdafuseError(st, "adafuse_prefill_group_workspace_bytes")
+        return int(n.value)
+
+    def prefill_group(self, mats, x, idx, gates, scale, ys=None, workspace=None, stream=None):
+        """adafuse_prefill_group: the matrices `mats` (same input width) applied to x bf16 [T][in] with per-token
+        decisions idx / gates (device) -> list of y fp32 [T][out_i]."""
+        import torch
+        T, k = idx.shape
+        assert x.dtype == torch.bfloat16 and x.is_contiguous() and x.shape[0] == T
+        assert idx.is_contiguous() and gates.is_contiguous() and gates.shape == idx.shape
+        if ys is None:
+            ys = [torch.empty((T, self._keep[m][0].shape[0] if 0 <= m < len(self._keep) else 0), dtype=torch.float32,
+                              device=x.device) for m in mats]
+        if workspace is None:
+            workspace = torch.empty(max(16, self.prefill_group_workspace_bytes(mats, T, k)), dtype=torch.uint8, device=x.device)
+        arr = (C.c_int32 * len(mats))(*mats)
+        yp = (C.c_void_p * len(mats))(*[_ptr(y) for y in ys])
+        st = load_library().adafuse_prefill_group(self._h, arr, len(mats), _ptr(x), T, _ptr(idx), _ptr(gates), k, scale, yp,
+                                                  _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                  _stream_handle(stream))
+        if st != 0:
+            raise AdafuseError(st, "adafuse_prefill_group")
+        return ys
 
     def close(self):
         if self._h:

@@ -663,83 +663,222 @@ PrefillCut prefill_cut(int T, int rows, int in)
     return c;
 }
 
+// Two forms.  FEW tokens (at most four token tiles: 512, measured level with the other form there): the bank products and the base products of ALL
+// matrices of the group share ONE launch, cut into the same number of parts so that their workgroups
+// take equally long, and a second kernel sums the parts and adds the adapters in fp32 -- two launches
+// for the group, no bf16 pair, no dependent chain of four small kernels per matrix (at a hundred tokens a
+// launch costs more than streaming a 4096 x 4096 matrix).  MANY tokens: matrix by matrix, the adapters
+// as further inner dimension of the base product on the matrix cores (bank product, gate kernel, base
+// product, sum of the parts if there are any).
+constexpr int kPfFewTiles = 4;
+inline int prefill_units8(int units) { return ((units + 7) / 8) * 8; }
+
 struct PrefillPlan {
-    PrefillCut down, up;
+    bool few;
+    int n;
+    // few-token form: one cut for every product of the group
+    int m_tiles, splits, chunks_per_split, bank_strips;
+    int strips[kPfMaxGroup];
+    uint64_t u_bytes;                 // one bank product's parts (16-byte multiple)
+    uint64_t w_bytes[kPfMaxGroup];    // one base product's parts
+    // many-token form, per matrix
+    PrefillCut down[kPfMaxGroup], up[kPfMaxGroup];
     int rp;
     uint64_t plane;        // bytes of one bf16 plane of the scaled down-projections
-    uint64_t parts_bytes;  // fp32 parts of the split products (the two passes share the space)
+    uint64_t parts_bytes;  // fp32 parts (the two passes and all matrices of the group share the space)
+    uint64_t total() const
+    {
+        if (!few) return 2 * plane + parts_bytes;
+        uint64_t t = 0;
+        for (int i = 0; i < n; ++i) t += u_bytes + w_bytes[i];
+        return t;
+    }
 };
 
-PrefillPlan prefill_plan(const adafuse_ctx *ctx, const adafuse_matrix_desc &m, int T, int k)
+PrefillPlan prefill_plan(const adafuse_ctx *ctx, const int32_t *mats, int n, int T, int k)
 {
-    PrefillPlan pl;
+    PrefillPlan pl{};
+    pl.n = n;
+    const int bank_rows = ctx->E * ctx->r;
+    const int in = ctx->mats[(size_t)mats[0]].in;
+    pl.m_tiles = (T + kPfTileTokens - 1) / kPfTileTokens;
+    pl.few = pl.m_tiles <= kPfFewTiles;
+    if (pl.few) {
+        pl.bank_strips = (bank_rows + kPfTileRows - 1) / kPfTileRows;
+        int total_strips = 0;
+        for (int i = 0; i < n; ++i) {
+            pl.strips[i] = (ctx->mats[(size_t)mats[i]].out + kPfTileRows - 1) / kPfTileRows;
+            total_strips += pl.strips[i] + pl.bank_strips;
+        }
+        const int chunks = (in + kPfChunk - 1) / kPfChunk;
+        // as many parts as keep ALL products in one wave of workgroups (one is resident per CU; a single
+        // workgroup more is a second round for the launch), counted the way the launch rounds each
+        // product's workgroups up to the 8 XCDs
+        int want = std::max(1, std::min(256 / (total_strips * pl.m_tiles), std::min(kPfMaxSplits, chunks / 2)));
+        for (;; --want) {
+            pl.chunks_per_split = (chunks + want - 1) / want;
+            pl.splits = (chunks + pl.chunks_per_split - 1) / pl.chunks_per_split;
+            int grid = 0;
+            for (int i = 0; i < n; ++i)
+                grid += (prefill_units8(pl.strips[i] * pl.splits) + prefill_units8(pl.bank_strips * pl.splits)) * pl.m_tiles;
+            if (grid <= 256 || want == 1) break;
+        }
+        pl.u_bytes = ((uint64_t)pl.splits * T * bank_rows * 4u + 15u) & ~15ull;
+        for (int i = 0; i < n; ++i)
+            pl.w_bytes[i] = ((uint64_t)pl.splits * T * ctx->mats[(size_t)mats[i]].out * 4u + 15u) & ~15ull;
+        return pl;
+    }
     pl.rp = ctx->r < 8 ? 8 : ctx->r;  // a slot holds whole 16-byte pieces
     pl.plane = ((uint64_t)T * (uint64_t)k * (uint64_t)pl.rp * 2u + 15u) & ~15ull;
-    pl.down = prefill_cut(T, ctx->E * ctx->r, m.in);
-    pl.up = prefill_cut(T, m.out, m.in);
-    const uint64_t down_parts = (uint64_t)pl.down.splits * T * ctx->E * ctx->r * 4u;   // U is always a temporary
-    const uint64_t up_parts = pl.up.splits > 1 ? (uint64_t)pl.up.splits * T * m.out * 4u : 0u;
-    pl.parts_bytes = std::max(down_parts, up_parts);
+    for (int i = 0; i < n; ++i) {
+        const adafuse_matrix_desc &m = ctx->mats[(size_t)mats[i]];
+        pl.down[i] = prefill_cut(T, bank_rows, m.in);
+        pl.up[i] = prefill_cut(T, m.out, m.in);
+        const uint64_t down_parts = (uint64_t)pl.down[i].splits * T * bank_rows * 4u;   // U is always a temporary
+        const uint64_t up_parts = pl.up[i].splits > 1 ? (uint64_t)pl.up[i].splits * T * m.out * 4u : 0u;
+        pl.parts_bytes = std::max(pl.parts_bytes, std::max(down_parts, up_parts));
+    }
     return pl;
+}
+
+adafuse_status prefill_group_checks(const adafuse_ctx *ctx, const int32_t *mats, int32_t n, int32_t T, int32_t k)
+{
+    if (!ctx || !mats) return ADAFUSE_ERR_NULL;
+    if (n < 1 || n > kPfMaxGroup || T < 0 || k < 1 || k > ctx->k_max) return ADAFUSE_ERR_ARG;
+    for (int i = 0; i < n; ++i) {
+        if (mats[i] < 0 || mats[i] >= (int32_t)ctx->mats.size()) return ADAFUSE_ERR_ARG;
+        if (ctx->mats[(size_t)mats[i]].in != ctx->mats[(size_t)mats[0]].in) return ADAFUSE_ERR_SHAPE;  // one X for all
+        for (int j = 0; j < i; ++j)
+            if (mats[j] == mats[i]) return ADAFUSE_ERR_ARG;
+    }
+    return ADAFUSE_OK;
 }
 
 }  // namespace
 
+adafuse_status adafuse_prefill_group_workspace_bytes(const adafuse_ctx *ctx, const int32_t *mats, int32_t n, int32_t T,
+                                                     int32_t k, size_t *bytes)
+{
+    if (!bytes) return ADAFUSE_ERR_NULL;
+    const adafuse_status st = prefill_group_checks(ctx, mats, n, T, k);
+    if (st != ADAFUSE_OK) return st;
+    *bytes = T == 0 ? 0 : (size_t)prefill_plan(ctx, mats, n, T, k).total();
+    return ADAFUSE_OK;
+}
+
 adafuse_status adafuse_prefill_workspace_bytes(const adafuse_ctx *ctx, int32_t mat, int32_t T, int32_t k, size_t *bytes)
 {
-    if (!ctx || !bytes) return ADAFUSE_ERR_NULL;
-    if (mat < 0 || mat >= (int32_t)ctx->mats.size() || T < 0 || k < 1 || k > ctx->k_max) return ADAFUSE_ERR_ARG;
-    if (T == 0) {
-        *bytes = 0;
-        return ADAFUSE_OK;
+    return adafuse_prefill_group_workspace_bytes(ctx, &mat, 1, T, k, bytes);
+}
+
+adafuse_status adafuse_prefill_group(adafuse_ctx *ctx, const int32_t *mats, int32_t n, const void *x, int32_t T,
+                                     const int32_t *idx, const float *gates, int32_t k, float scale, float *const *y,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const adafuse_status st = prefill_group_checks(ctx, mats, n, T, k);
+    if (st != ADAFUSE_OK) return st;
+    if (ctx->inplace) return ADAFUSE_ERR_ARG;  // needs the unmodified base weights
+    if (T == 0) return ADAFUSE_OK;             // no tokens: nothing to read or write
+    if (!x || !idx || !gates || !y || !workspace) return ADAFUSE_ERR_NULL;
+    if (!aligned16(x) || !aligned16(workspace)) return ADAFUSE_ERR_ALIGN;
+    for (int i = 0; i < n; ++i) {
+        if (!y[i]) return ADAFUSE_ERR_NULL;
+        if (!aligned16(y[i])) return ADAFUSE_ERR_ALIGN;
     }
-    const PrefillPlan pl = prefill_plan(ctx, ctx->mats[(size_t)mat], T, k);
-    *bytes = (size_t)(2 * pl.plane + pl.parts_bytes);
-    return ADAFUSE_OK;
+    const PrefillPlan pl = prefill_plan(ctx, mats, n, T, k);
+    if (workspace_bytes < pl.total()) return ADAFUSE_ERR_ARG;
+    const int in = ctx->mats[(size_t)mats[0]].in;
+    // the kernels address X and the workspace planes through 32-bit descriptors and offsets
+    if ((uint64_t)T * (uint64_t)in * 2u >= (1ull << 31) || pl.plane >= (1ull << 31)) return ADAFUSE_ERR_SHAPE;
+    if (!on_ctx_device(ctx)) return ADAFUSE_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const uint16_t *xp = static_cast<const uint16_t *>(x);
+    const int bank_rows = ctx->E * ctx->r;
+    auto grid_of = [](int strips, int splits, int m_tiles) { return prefill_units8(strips * splits) * m_tiles; };
+    auto close_batch = [](PrefillBatch &b, int used) {
+        for (int j = used; j < kPfMaxProducts; ++j) b.end[j] = b.end[used - 1];
+    };
+
+    if (pl.few) {
+        // 1. every X W^T and every U = X A^T (whole bank), in parts, one launch
+        PrefillBatch batch{};
+        PrefillFinishBatch fin{};
+        char *at = static_cast<char *>(workspace);
+        int grid = 0;
+        for (int i = 0; i < n; ++i) {
+            const adafuse_matrix_desc &m = ctx->mats[(size_t)mats[i]];
+            float *u_parts = reinterpret_cast<float *>(at);
+            float *w_parts = reinterpret_cast<float *>(at + pl.u_bytes);
+            at += pl.u_bytes + pl.w_bytes[i];
+            batch.g[2 * i] = PrefillGemm{static_cast<const uint16_t *>(m.w_base), xp, w_parts, m.out, m.ldw, m.in, T,
+                                         pl.splits, pl.chunks_per_split, pl.m_tiles, pl.strips[i],
+                                         nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0};
+            grid += grid_of(pl.strips[i], pl.splits, pl.m_tiles);
+            batch.end[2 * i] = grid;
+            batch.g[2 * i + 1] = PrefillGemm{static_cast<const uint16_t *>(m.a_bank), xp, u_parts, bank_rows, m.in, m.in, T,
+                                             pl.splits, pl.chunks_per_split, pl.m_tiles, pl.bank_strips,
+                                             nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0};
+            grid += grid_of(pl.bank_strips, pl.splits, pl.m_tiles);
+            batch.end[2 * i + 1] = grid;
+            fin.f[i] = PrefillFinish{w_parts, u_parts, static_cast<const uint16_t *>(m.b_bank), idx, gates, y[i],
+                                     T, m.out, ctx->E, ctx->r, k, pl.splits, scale};
+        }
+        close_batch(batch, 2 * n);
+        hipLaunchKernelGGL(prefill_gemm_kernel, dim3((unsigned)grid), dim3(256), 0, s, batch);
+        // 2. parts summed, adapters added
+        int max_out = 0;
+        for (int i = 0; i < n; ++i) max_out = std::max(max_out, ctx->mats[(size_t)mats[i]].out);
+        for (int i = n; i < kPfMaxGroup; ++i) fin.f[i] = fin.f[0];
+        const dim3 fin_grid((unsigned)((max_out + 1023) / 1024), (unsigned)T, (unsigned)n);
+        if (pl.splits <= 2) hipLaunchKernelGGL(prefill_finish_kernel<2>, fin_grid, dim3(256), 0, s, fin);
+        else if (pl.splits <= 4) hipLaunchKernelGGL(prefill_finish_kernel<4>, fin_grid, dim3(256), 0, s, fin);
+        else if (pl.splits <= 8) hipLaunchKernelGGL(prefill_finish_kernel<8>, fin_grid, dim3(256), 0, s, fin);
+        else if (pl.splits <= 16) hipLaunchKernelGGL(prefill_finish_kernel<16>, fin_grid, dim3(256), 0, s, fin);
+        else hipLaunchKernelGGL(prefill_finish_kernel<kPfMaxSplits>, fin_grid, dim3(256), 0, s, fin);
+        return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
+    }
+
+    uint16_t *z_hi = static_cast<uint16_t *>(workspace);
+    uint16_t *z_lo = z_hi + pl.plane / 2;
+    float *parts = reinterpret_cast<float *>(z_lo + pl.plane / 2);
+    for (int i = 0; i < n; ++i) {
+        const adafuse_matrix_desc &m = ctx->mats[(size_t)mats[i]];
+        const PrefillCut &dc = pl.down[i], &uc = pl.up[i];
+        // 1. U = X A^T over the whole bank, in parts
+        PrefillBatch down{};
+        down.g[0] = PrefillGemm{static_cast<const uint16_t *>(m.a_bank), xp, parts, bank_rows, m.in, m.in, T,
+                                dc.splits, dc.chunks_per_split, dc.m_tiles, dc.strips,
+                                nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0};
+        down.end[0] = grid_of(dc.strips, dc.splits, dc.m_tiles);
+        close_batch(down, 1);
+        hipLaunchKernelGGL(prefill_gemm_kernel, dim3((unsigned)down.end[0]), dim3(256), 0, s, down);
+        // 2. the selected experts' columns, scaled by s g, as bf16 pairs
+        PrefillGate gate{parts, idx, gates, z_hi, z_lo, T, ctx->E, ctx->r, pl.rp, k, dc.splits, scale};
+        const int64_t n_z = (int64_t)T * k * pl.rp;
+        hipLaunchKernelGGL(prefill_gate_kernel, dim3((unsigned)((n_z + 255) / 256)), dim3(256), 0, s, gate);
+        // 3. X W^T with the adapters as further inner dimension; 4. its parts summed
+        PrefillBatch up{};
+        up.g[0] = PrefillGemm{static_cast<const uint16_t *>(m.w_base), xp, uc.splits > 1 ? parts : y[i], m.out, m.ldw, m.in, T,
+                              uc.splits, uc.chunks_per_split, uc.m_tiles, uc.strips,
+                              static_cast<const uint16_t *>(m.b_bank), idx, z_hi, z_lo, ctx->E, ctx->r, pl.rp, k};
+        up.end[0] = grid_of(uc.strips, uc.splits, uc.m_tiles);
+        close_batch(up, 1);
+        hipLaunchKernelGGL(prefill_gemm_kernel, dim3((unsigned)up.end[0]), dim3(256), 0, s, up);
+        if (uc.splits > 1) {
+            const int64_t n_y = (int64_t)T * m.out;
+            hipLaunchKernelGGL(prefill_sum_kernel, dim3((unsigned)((n_y + 1023) / 1024)), dim3(256), 0, s, parts, y[i], n_y, uc.splits);
+        }
+    }
+    return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
 }
 
 adafuse_status adafuse_prefill(adafuse_ctx *ctx, int32_t mat, const void *x, int32_t T, const int32_t *idx,
                                const float *gates, int32_t k, float scale, float *y, void *workspace,
                                size_t workspace_bytes, void *hip_stream)
 {
-    if (!ctx) return ADAFUSE_ERR_NULL;
-    if (mat < 0 || mat >= (int32_t)ctx->mats.size() || T < 0 || k < 1 || k > ctx->k_max) return ADAFUSE_ERR_ARG;
-    if (ctx->inplace) return ADAFUSE_ERR_ARG;  // needs the unmodified base weights
-    if (T == 0) return ADAFUSE_OK;             // no tokens: nothing to read or write
-    if (!x || !idx || !gates || !y || !workspace) return ADAFUSE_ERR_NULL;
-    if (!aligned16(x) || !aligned16(y) || !aligned16(workspace)) return ADAFUSE_ERR_ALIGN;
-    const adafuse_matrix_desc &m = ctx->mats[(size_t)mat];
-    const PrefillPlan pl = prefill_plan(ctx, m, T, k);
-    if (workspace_bytes < 2 * pl.plane + pl.parts_bytes) return ADAFUSE_ERR_ARG;
-    // the kernels address X and the workspace planes through 32-bit descriptors and offsets
-    if ((uint64_t)T * (uint64_t)m.in * 2u >= (1ull << 31) || pl.plane >= (1ull << 31)) return ADAFUSE_ERR_SHAPE;
-    if (!on_ctx_device(ctx)) return ADAFUSE_ERR_ARG;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    uint16_t *z_hi = static_cast<uint16_t *>(workspace);
-    uint16_t *z_lo = z_hi + pl.plane / 2;
-    float *parts = reinterpret_cast<float *>(z_lo + pl.plane / 2);
-    const uint16_t *xp = static_cast<const uint16_t *>(x);
-    auto grid_of = [](const PrefillCut &c) { return dim3((unsigned)(((c.strips * c.splits + 7) / 8) * 8 * c.m_tiles)); };
-
-    // 1. U = X A^T over the whole bank, in parts
-    PrefillGemm down{static_cast<const uint16_t *>(m.a_bank), xp, parts, ctx->E * ctx->r, m.in, m.in, T,
-                     pl.down.splits, pl.down.chunks_per_split, pl.down.m_tiles, pl.down.strips,
-                     nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0};
-    hipLaunchKernelGGL(prefill_gemm_kernel, grid_of(pl.down), dim3(256), 0, s, down);
-    // 2. the selected experts' columns, scaled by s g, as bf16 pairs
-    PrefillGate gate{parts, idx, gates, z_hi, z_lo, T, ctx->E, ctx->r, pl.rp, k, pl.down.splits, scale};
-    const int64_t n_z = (int64_t)T * k * pl.rp;
-    hipLaunchKernelGGL(prefill_gate_kernel, dim3((unsigned)((n_z + 255) / 256)), dim3(256), 0, s, gate);
-    // 3. X W^T with the adapters as further inner dimension; 4. its parts summed
-    PrefillGemm up{static_cast<const uint16_t *>(m.w_base), xp, pl.up.splits > 1 ? parts : y, m.out, m.ldw, m.in, T,
-                   pl.up.splits, pl.up.chunks_per_split, pl.up.m_tiles, pl.up.strips,
-                   static_cast<const uint16_t *>(m.b_bank), idx, z_hi, z_lo, ctx->E, ctx->r, pl.rp, k};
-    hipLaunchKernelGGL(prefill_gemm_kernel, grid_of(pl.up), dim3(256), 0, s, up);
-    if (pl.up.splits > 1) {
-        const int64_t n_y = (int64_t)T * m.out;
-        hipLaunchKernelGGL(prefill_sum_kernel, dim3((unsigned)((n_y + 1023) / 1024)), dim3(256), 0, s, parts, y, n_y, pl.up.splits);
-    }
-    return hipGetLastError() == hipSuccess ? ADAFUSE_OK : ADAFUSE_ERR_HIP;
+    float *ys[1] = {y};
+    if (ctx && !y && T != 0) return ADAFUSE_ERR_NULL;
+    return adafuse_prefill_group(ctx, &mat, 1, x, T, idx, gates, k, scale, ys, workspace, workspace_bytes, hip_stream);
 }
 
 adafuse_status adafuse_hbm_probe(adafuse_ctx *ctx, int32_t direction, void *hip_stream)

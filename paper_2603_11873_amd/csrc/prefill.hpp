@@ -124,11 +124,21 @@ __device__ __forceinline__ void pf_multiply(pf_float16_t (&acc)[4][2], const uin
         for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int c = 0; c < 2; ++c)
-                acc[b][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(mv[c]), as_operand(xv[b]), acc[b][c], 0, 0, 0);
+                acc[b][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(xv[b]), as_operand(mv[c]), acc[b][c], 0, 0, 0);
     }
 }
 
-__global__ __launch_bounds__(256) void prefill_gemm_kernel(PrefillGemm p)
+// One launch can carry several products over the same X (workgroups [end[i-1], end[i]) run product i):
+// with a tile or two of tokens the down-projection through a bank and the base product are independent,
+// as are the matrices of a layer that share an input (q, k, v; gate, up), and each alone is too small to
+// fill the chip for long.
+constexpr int kPfMaxProducts = 8;
+struct PrefillBatch {
+    PrefillGemm g[kPfMaxProducts];
+    int32_t end[kPfMaxProducts];  // running totals of the products' workgroup counts (multiples of 8); unused entries repeat the last
+};
+
+__global__ __launch_bounds__(256) void prefill_gemm_kernel(PrefillBatch batch)
 {
     // three stages (144 KB: one workgroup per CU, two chunks -- 64 KB of the matrix -- in flight while a
     // third is multiplied), each its own pair of arrays: the compiler then knows that reading one stage
@@ -136,11 +146,17 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(PrefillGemm p)
     __shared__ __align__(16) uint16_t s_x0[kPfTileTokens * kPfChunk], s_x1[kPfTileTokens * kPfChunk], s_x2[kPfTileTokens * kPfChunk];
     __shared__ __align__(16) uint16_t s_m0[kPfTileRows * kPfChunk], s_m1[kPfTileRows * kPfChunk], s_m2[kPfTileRows * kPfChunk];
 
+    int which = 0;  // uniform: a scan over scalar registers
+#pragma unroll
+    for (int j = 0; j + 1 < kPfMaxProducts; ++j)
+        if ((int)blockIdx.x >= batch.end[j]) which = j + 1;
+    const PrefillGemm &p = batch.g[which];
+    const int block = (int)blockIdx.x - (which ? batch.end[which - 1] : 0);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, h = lane >> 5;
     // workgroup i runs on XCD i % 8: the token tiles of one (strip, part) follow each other on one XCD,
     // so the second and later ones find the matrix lines in that XCD's L2
-    const int xcd = blockIdx.x % 8, q = blockIdx.x / 8;
+    const int xcd = block % 8, q = block / 8;
     const int unit = (q / p.m_tiles) * 8 + xcd, m_tile = q % p.m_tiles;
     if (unit >= p.strips * p.splits) return;
     const int strip = unit / p.splits, part = unit % p.splits;
@@ -244,34 +260,30 @@ __global__ __launch_bounds__(256) void prefill_gemm_kernel(PrefillGemm p)
                 for (int b = 0; b < 4; ++b)
 #pragma unroll
                     for (int c = 0; c < 2; ++c) {
-                        acc[b][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(bv[c]), as_operand(lv[b]), acc[b][c], 0, 0, 0);
-                        acc[b][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(bv[c]), as_operand(hv[b]), acc[b][c], 0, 0, 0);
+                        acc[b][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(lv[b]), as_operand(bv[c]), acc[b][c], 0, 0, 0);
+                        acc[b][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(hv[b]), as_operand(bv[c]), acc[b][c], 0, 0, 0);
                     }
             }
         }
     }
     if (!has_rows) return;
 
-    // accumulator entries 4 q .. 4 q + 3 of block (b, c): token t0 + 32 b + n, rows ow + 32 c + 8 q + 4 h + 0..3
+    // The token operand goes first into the matrix core, so a lane holds ONE output row and its 16
+    // accumulator entries of block (b, c) are tokens: entry 4 q + u is token t0 + 32 b + 8 q + 4 h + u, row
+    // ow + 32 c + n.  A store instruction then writes, per half-wave, 32 consecutive rows of one token: a
+    // whole 128-byte line (one token per lane would scatter 16-byte pieces over 64 lines, which the
+    // memory side pays for with partial-line writes: measured 8 us of a 20 us launch at 100 tokens).
     float *dst0 = p.out + (size_t)part * p.T * p.rows;
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-        const int t = t0 + 32 * b + n;
-        if (t >= p.T) continue;
+    for (int c = 0; c < 2; ++c) {
+        const int oo = ow + 32 * c + n;
+        if (oo >= p.rows) continue;
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int qq = 0; qq < 4; ++qq) {
-                const int oo = ow + 32 * c + 8 * qq + 4 * h;
-                float *dst = dst0 + (size_t)t * p.rows + oo;
-                if (oo + 3 < p.rows && (p.rows & 3) == 0) {
-                    *reinterpret_cast<float4_t *>(dst) =
-                        float4_t{acc[b][c][4 * qq], acc[b][c][4 * qq + 1], acc[b][c][4 * qq + 2], acc[b][c][4 * qq + 3]};
-                } else {
-#pragma unroll
-                    for (int u = 0; u < 4; ++u)
-                        if (oo + u < p.rows) dst[u] = acc[b][c][4 * qq + u];
-                }
+            for (int v = 0; v < 16; ++v) {
+                const int t = t0 + 32 * b + 8 * (v / 4) + 4 * h + v % 4;
+                if (t < p.T) __builtin_nontemporal_store(acc[b][c][v], dst0 + (size_t)t * p.rows + oo);
             }
     }
 }
@@ -299,6 +311,138 @@ __global__ __launch_bounds__(256) void prefill_sum_kernel(const float *parts, fl
             for (int q = 1; q < splits; ++q) s += parts[(size_t)q * n + j];
             y[j] = s;
         }
+    }
+}
+
+// Last step of the few-token form: y[t][o] = sum of the base product's parts, in order, plus the
+// adapters in fp32 on the vector ALU,
+//   sum_j (s g_{t,j}) sum_rho B_{e_{t,j}}[o][rho] * u[t][e_{t,j} r + rho],   u = the bank product's parts summed in order.
+// A workgroup takes one token and 1024 output rows (4 per thread); the token's k r scaled
+// down-projections are formed once in LDS.  A repeated selection of an expert simply adds twice.
+struct PrefillFinish {
+    const float *w_parts;  // [splits][T][rows]
+    const float *u_parts;  // [splits][T][E r]
+    const uint16_t *b_bank;
+    const int32_t *idx;
+    const float *gates;
+    float *y;
+    int32_t T, rows, E, r, k, splits;
+    float scale;
+};
+
+constexpr int kPfMaxGroup = 4;  // matrices that share an input, finished by one launch (grid z)
+struct PrefillFinishBatch {
+    PrefillFinish f[kPfMaxGroup];
+};
+
+// NS: slots for the parts (at least the number of parts; unused slots add +0): registers, and with them how many
+// workgroups a CU holds while each walks its chain of dependent loads.  That chain is kept to three round
+// trips -- the routing decision (scalar loads); the parts of both products, all requested at once; after
+// the barrier the rows of the selected B_e, four 16-byte pieces at a time -- because at a hundred tokens
+// this kernel is nothing but latency.
+template <int NS>
+__global__ __launch_bounds__(256) void prefill_finish_kernel(PrefillFinishBatch batch)
+{
+    __shared__ float s_z[kMaxTopK * 128];
+    const PrefillFinish p = batch.f[blockIdx.z];
+    const int t = blockIdx.y;
+    const int kr = p.k * p.r;
+    const int log_r = __builtin_ctz((unsigned)p.r);  // ranks are powers of two
+    const int o0 = 1024 * blockIdx.x + 4 * threadIdx.x;
+    const size_t n_y = (size_t)p.T * p.rows, at = (size_t)t * p.rows + o0;
+    const bool whole = o0 + 3 < p.rows && (p.rows & 3) == 0;  // four rows, 16-byte aligned in every part and in B_e
+    int ex[kMaxTopK];   // the token's decision: uniform, scalar loads
+    float cf[kMaxTopK];
+#pragma unroll
+    for (int j = 0; j < kMaxTopK; ++j) {
+        ex[j] = j < p.k ? clamp_expert(p.idx[(size_t)t * p.k + j], p.E) : 0;
+        cf[j] = j < p.k ? p.scale * p.gates[(size_t)t * p.k + j] : 0.0f;
+    }
+    // the base product's parts: independent of the decision, requested first
+    float4_t wv[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+        wv[s] = s < p.splits && whole ? *reinterpret_cast<const float4_t *>(p.w_parts + (size_t)s * n_y + at) : float4_t{0.f, 0.f, 0.f, 0.f};
+    // the token's k r scaled down-projections, once per workgroup
+    const size_t n_u = (size_t)p.T * p.E * p.r;
+    for (int q = threadIdx.x; q < kr; q += 256) {
+        const int j = q >> log_r, rho = q & (p.r - 1);
+        int e = 0;
+        float c = 0.0f;
+#pragma unroll
+        for (int jj = 0; jj < kMaxTopK; ++jj)
+            if (jj == j) e = ex[jj], c = cf[jj];
+        const size_t ua = ((size_t)t * p.E + e) * p.r + rho;
+        float v[NS];  // all parts requested before the first addition; unused slots add +0
+#pragma unroll
+        for (int s = 0; s < NS; ++s) v[s] = s < p.splits ? p.u_parts[(size_t)s * n_u + ua] : 0.0f;
+        float u = v[0];
+#pragma unroll
+        for (int s = 1; s < NS; ++s) u += v[s];
+        s_z[q] = c * u;
+    }
+    __syncthreads();
+    if (o0 >= p.rows) return;
+    float acc[4];
+    if (whole) {
+        float4_t sum = wv[0];
+#pragma unroll
+        for (int s = 1; s < NS; ++s) sum += wv[s];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] = sum[i];
+        // the thread's four rows of B_e are 4 r contiguous bf16: r / 2 pieces of 8, element f of them is
+        // row f / r, rank index f % r; rank indices of a row are taken in ascending order
+        const int pieces = p.r >> 1;
+#pragma unroll
+        for (int j = 0; j < kMaxTopK; ++j) {
+            if (j >= p.k) break;
+            const uint4_t *bp = reinterpret_cast<const uint4_t *>(p.b_bank + ((size_t)ex[j] * p.rows + o0) * p.r);
+            const float *z = s_z + (j << log_r);
+            for (int pc = 0; pc < pieces; pc += 4) {
+                uint4_t bv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) bv[u] = pc + u < pieces ? bp[pc + u] : uint4_t{0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (pc + u >= pieces) break;
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {  // four elements: one row for every rank
+                        const int f = 8 * (pc + u) + 4 * half;
+                        const int i = f >> log_r, rho = f & (p.r - 1);
+                        float a = 0.0f;
+#pragma unroll
+                        for (int ii = 0; ii < 4; ++ii)  // (one of the four accumulators: a select, not an indexed register)
+                            if (ii == i) a = acc[ii];
+                        a = __builtin_fmaf(bf16_lo(bv[u][2 * half]), z[rho], a);
+                        a = __builtin_fmaf(bf16_hi(bv[u][2 * half]), z[rho + 1], a);
+                        a = __builtin_fmaf(bf16_lo(bv[u][2 * half + 1]), z[rho + 2], a);
+                        a = __builtin_fmaf(bf16_hi(bv[u][2 * half + 1]), z[rho + 3], a);
+#pragma unroll
+                        for (int ii = 0; ii < 4; ++ii)
+                            if (ii == i) acc[ii] = a;
+                    }
+                }
+            }
+        }
+        *reinterpret_cast<float4_t *>(p.y + at) = float4_t{acc[0], acc[1], acc[2], acc[3]};
+        return;
+    }
+    // rows at the edge of a matrix whose height is not a multiple of 4: element by element
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (o0 + i >= p.rows) continue;
+        float a = p.w_parts[at + i];
+        for (int s = 1; s < p.splits; ++s) a += p.w_parts[(size_t)s * n_y + at + i];
+        for (int j = 0; j < p.k; ++j) {
+            int e = 0;
+#pragma unroll
+            for (int jj = 0; jj < kMaxTopK; ++jj)
+                if (jj == j) e = ex[jj];
+            const uint16_t *brow = p.b_bank + ((size_t)e * p.rows + o0 + i) * p.r;
+            const float *z = s_z + (j << log_r);
+            for (int rho = 0; rho < p.r; ++rho) a = __builtin_fmaf(__uint_as_float((uint32_t)brow[rho] << 16), z[rho], a);
+        }
+        p.y[at + i] = a;
     }
 }
 

@@ -163,6 +163,64 @@ def test_many_tokens_take_the_128_token_tiles(oracle):
     ctx.close()
 
 
+@pytest.mark.parametrize("T", [1, 100, 129, 512, 600])
+def test_group_of_matrices_that_share_an_input(oracle, T):
+    """Three matrices of different heights (one ragged) over one input, as the q, k and v projections of a
+    GQA layer: one call for the group, every output against the oracle; token counts on both sides of the
+    few-token / many-token switch (512) and of a tile boundary."""
+    dev = torch.device("cuda:0")
+    g = torch.Generator().manual_seed(900 + T)
+    in_, E, r, k = 320, 5, 8, 2
+    outs = [512, 130, 64]
+    mats = []
+    for out in outs:
+        wb = (0.02 * torch.randn((out, in_), generator=g)).to(torch.bfloat16).to(dev)
+        a = (in_ ** -0.5 * torch.randn((E, r, in_), generator=g)).to(torch.bfloat16).to(dev)
+        b = (0.05 * torch.randn((E, out, r), generator=g)).to(torch.bfloat16).to(dev)
+        mats.append((wb, torch.empty_like(wb), a, b))
+    x = torch.randn((T, in_), generator=g).to(torch.bfloat16).to(dev)
+    idx = torch.stack([torch.randperm(E, generator=g)[:k] for _ in range(T)]).to(torch.int32)
+    idx[::7, 1] = idx[::7, 0]
+    gates = torch.softmax(torch.randn((T, k), generator=g), 1)
+    ctx = af.Context(mats, k)
+    ys = [torch.full((T, out), float("nan"), dtype=torch.float32, device=dev) for out in outs]
+    ctx.prefill_group([0, 1, 2], x, idx.to(dev), gates.to(dev), 2.0, ys=ys)
+    torch.cuda.synchronize()
+    tokens = sorted(set([0, T // 2, T - 1] + [t for t in (127, 128, 255, 256, 511, 512) if t < T]))
+    for mat, y in zip(mats, ys):
+        _check(oracle, (mat[0], None, mat[2], mat[3]), x, idx.numpy(), gates.numpy(), 2.0, y, tokens)
+    # the group in another order writes the same bits: the cut does not depend on the order
+    ys2 = ctx.prefill_group([2, 0, 1], x, idx.to(dev), gates.to(dev), 2.0)
+    torch.cuda.synchronize()
+    for a, b in zip(ys, [ys2[1], ys2[2], ys2[0]]):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+    ctx.close()
+
+
+def test_group_refuses_what_it_cannot_do():
+    dev = torch.device("cuda:0")
+    mk = lambda o, i: (torch.zeros((o, i), dtype=torch.bfloat16, device=dev), torch.zeros((o, i), dtype=torch.bfloat16, device=dev),
+                       torch.zeros((4, 8, i), dtype=torch.bfloat16, device=dev), torch.zeros((4, o, 8), dtype=torch.bfloat16, device=dev))
+    ctx = af.Context([mk(64, 64), mk(128, 64), mk(64, 128), mk(32, 64), mk(16, 64), mk(8, 64)], 2)
+    x = torch.zeros((5, 64), dtype=torch.bfloat16, device=dev)
+    idx = torch.zeros((5, 2), dtype=torch.int32, device=dev)
+    gates = torch.zeros((5, 2), dtype=torch.float32, device=dev)
+    with pytest.raises(af.AdafuseError):
+        ctx.prefill_group([0, 2], x, idx, gates, 2.0)            # different input widths
+    with pytest.raises(af.AdafuseError):
+        ctx.prefill_group([0, 0], x, idx, gates, 2.0)            # the same matrix twice
+    with pytest.raises(af.AdafuseError):
+        ctx.prefill_group([0, 1, 3, 4, 5], x, idx, gates, 2.0)   # more than four
+    with pytest.raises(af.AdafuseError):
+        ctx.prefill_group([], x, idx, gates, 2.0)
+    with pytest.raises(af.AdafuseError):
+        ctx.prefill_group([0, 9], x, idx, gates, 2.0)            # no such matrix
+    ys = ctx.prefill_group([0, 1, 3, 4], x, idx, gates, 2.0)     # four is fine
+    torch.cuda.synchronize()
+    assert [tuple(y.shape) for y in ys] == [(5, 64), (5, 128), (5, 32), (5, 16)] and all(bool((y == 0).all()) for y in ys)
+    ctx.close()
+
+
 def test_prefill_refuses_what_it_cannot_do():
     dev = torch.device("cuda:0")
     w = torch.zeros((64, 64), dtype=torch.bfloat16, device=dev)
