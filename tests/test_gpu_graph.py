@@ -83,3 +83,61 @@ def test_captured_decode_step_replays_correctly(oracle, kernel, rank):
     for (_, ww, _, _), rep in zip(m.mats, replayed):
         assert torch.equal(ww.view(torch.int16), rep.view(torch.int16))
     m.close()
+
+
+@pytest.mark.parametrize("T", [100, 600])
+def test_captured_prefill_replays_correctly(T):
+    """adafuse_pregate + adafuse_prefill_group (three matrices over one input) captured once and replayed on
+    new inputs, in the few-token form (two launches) and in the many-token form; every replay equals the
+    eager call on the same inputs bit for bit (fixed order of every sum), with eager work in between."""
+    dev = torch.device("cuda:0")
+    g = torch.Generator().manual_seed(40 + T)
+    in_, E, r, k = 320, 6, 8, 2
+    outs = [512, 130, 64]
+    mats = []
+    for out in outs:
+        wb = (0.02 * torch.randn((out, in_), generator=g)).to(torch.bfloat16).to(dev)
+        a = (in_ ** -0.5 * torch.randn((E, r, in_), generator=g)).to(torch.bfloat16).to(dev)
+        b = (0.05 * torch.randn((E, out, r), generator=g)).to(torch.bfloat16).to(dev)
+        mats.append((wb, torch.empty_like(wb), a, b))
+    router = (0.02 * torch.randn((E, in_), generator=g)).to(torch.bfloat16).to(dev)
+    ctx = af.Context(mats, k)
+    xs = [torch.randn((T, in_), generator=g).to(torch.bfloat16).to(dev) for _ in range(3)]
+    x = torch.empty_like(xs[0])
+    idx = torch.zeros((T, k), dtype=torch.int32, device=dev)
+    gates = torch.zeros((T, k), dtype=torch.float32, device=dev)
+    ys = [torch.empty((T, out), dtype=torch.float32, device=dev) for out in outs]
+    ws = torch.empty(ctx.prefill_group_workspace_bytes([0, 1, 2], T, k), dtype=torch.uint8, device=dev)
+
+    def step():
+        s = torch.cuda.current_stream()
+        af.pregate(x, router, k, out=(idx, gates, None), stream=s)
+        ctx.prefill_group([0, 1, 2], x, idx, gates, 2.0, ys=ys, workspace=ws, stream=s)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        x.copy_(xs[0])
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for which in (1, 2, 1, 0):
+        x.copy_(xs[which])
+        for y in ys:
+            y.fill_(float("nan"))
+        ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = [y.clone() for y in ys]
+        assert all(bool(torch.isfinite(y).all()) for y in replayed)
+        for y in ys:
+            y.fill_(float("nan"))
+        step()
+        torch.cuda.synchronize()
+        for a, b in zip(ys, replayed):
+            assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+    ctx.close()
