@@ -104,28 +104,55 @@ __device__ __forceinline__ void pf_request(uint16_t *sx, uint16_t *sm, __amdgpu_
 constexpr int kPfRequests = kPfTileTokens / 32 + kPfTileRows / 32;  // transfers per wave and chunk
 
 // The wave's 128 tokens x 64 rows of one chunk: four k-steps, operands from LDS in the matrix-core layout.
-__device__ __forceinline__ void pf_multiply(pf_float16_t (&acc)[4][2], const uint16_t *sx, const uint16_t *sm, int wave, int n, int h)
+// The six operand reads of k-step s + 1 are issued before the eight matrix-core instructions of k-step s
+// (two register sets, and scheduling groups so that the compiler keeps that order): with one wave per SIMD
+// nothing else hides the LDS latency, and reads placed right in front of their use left the matrix cores
+// idle for two thirds of the time.
+struct PfOperands {
+    uint4_t mv[2], xv[4];
+};
+__device__ __forceinline__ void pf_read(PfOperands &o, const uint16_t *sx, const uint16_t *sm, int s, int wave, int n, int h)
+{
+    const int piece = 2 * s + h;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int mrow = 64 * wave + 32 * c + n;
+        o.mv[c] = *reinterpret_cast<const uint4_t *>(sm + 64 * mrow + 8 * (piece ^ (mrow % 8)));
+    }
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const int xrow = 32 * b + n;
+        o.xv[b] = *reinterpret_cast<const uint4_t *>(sx + 64 * xrow + 8 * (piece ^ (xrow % 8)));
+    }
+}
+__device__ __forceinline__ void pf_mfma(pf_float16_t (&acc)[4][2], const PfOperands &o)
 {
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const int piece = 2 * s + h;
-        uint4_t mv[2], xv[4];
+    for (int b = 0; b < 4; ++b)
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const int mrow = 64 * wave + 32 * c + n;
-            mv[c] = *reinterpret_cast<const uint4_t *>(sm + 64 * mrow + 8 * (piece ^ (mrow % 8)));
-        }
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int xrow = 32 * b + n;
-            xv[b] = *reinterpret_cast<const uint4_t *>(sx + 64 * xrow + 8 * (piece ^ (xrow % 8)));
-        }
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int c = 0; c < 2; ++c)
-                acc[b][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(xv[b]), as_operand(mv[c]), acc[b][c], 0, 0, 0);
-    }
+        for (int c = 0; c < 2; ++c)
+            acc[b][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_operand(o.xv[b]), as_operand(o.mv[c]), acc[b][c], 0, 0, 0);
+}
+__device__ __forceinline__ void pf_multiply(pf_float16_t (&acc)[4][2], const uint16_t *sx, const uint16_t *sm, int wave, int n, int h)
+{
+    constexpr int kDsRead = 0x100, kMfma = 0x008;
+    PfOperands o0, o1;
+    pf_read(o0, sx, sm, 0, wave, n, h);
+    __builtin_amdgcn_sched_group_barrier(kDsRead, 6, 0);
+    pf_read(o1, sx, sm, 1, wave, n, h);
+    __builtin_amdgcn_sched_group_barrier(kDsRead, 6, 0);
+    pf_mfma(acc, o0);
+    __builtin_amdgcn_sched_group_barrier(kMfma, 8, 0);
+    pf_read(o0, sx, sm, 2, wave, n, h);
+    __builtin_amdgcn_sched_group_barrier(kDsRead, 6, 0);
+    pf_mfma(acc, o1);
+    __builtin_amdgcn_sched_group_barrier(kMfma, 8, 0);
+    pf_read(o1, sx, sm, 3, wave, n, h);
+    __builtin_amdgcn_sched_group_barrier(kDsRead, 6, 0);
+    pf_mfma(acc, o0);
+    __builtin_amdgcn_sched_group_barrier(kMfma, 8, 0);
+    pf_mfma(acc, o1);
+    __builtin_amdgcn_sched_group_barrier(kMfma, 8, 0);
 }
 
 // One launch can carry several products over the same X (workgroups [end[i-1], end[i]) run product i):
