@@ -330,12 +330,17 @@ def test_full_size_models_sampled_rows(oracle, name):
     m.close()
 
 
-@pytest.mark.skipif(os.environ.get("ADAFUSE_FULL_CHECK") != "1",
-                    reason="minutes of oracle time per model: set ADAFUSE_FULL_CHECK=1 to run")
-@pytest.mark.parametrize("name", ["llama2_7b_attn", "llama2_7b_all", "llama3_8b_gqa_all", "llama2_13b_all"])
+_OPT_IN = pytest.mark.skipif(os.environ.get("ADAFUSE_FULL_CHECK") != "1",
+                             reason="minutes of oracle time per model: set ADAFUSE_FULL_CHECK=1 to run")
+
+
+@pytest.mark.parametrize("name", ["llama2_7b_attn", pytest.param("llama2_7b_all", marks=_OPT_IN),
+                                  pytest.param("llama3_8b_gqa_all", marks=_OPT_IN), pytest.param("llama2_13b_all", marks=_OPT_IN)])
 def test_full_size_models_every_element(oracle, name):
     """EVERY element of EVERY matrix of the full model after one token of the SWAP sequence
-    (token T/2, reached through the sequence's previous decision), streamed matrix by matrix."""
+    (token T/2, reached through the sequence's previous decision), streamed matrix by matrix.
+    The attention-only configuration (2.1e9 elements, about a minute of oracle time) always runs;
+    the three larger ones take 3 to 6 minutes each and are opt-in."""
     wl = wlmod.WORKLOADS[name]
     m = DeviceModel(wl, gen_device="cuda", sentinel=True)
     hidx, hg, idx, gates = oracle_decisions(oracle, m.hidden, m.router, wl.k)
