@@ -158,7 +158,7 @@ def prefill_bench(torch, af, ctx, wl, mats, hidden, router, T, stream, reps):
     hbm = (w_bytes + io_bytes) / sec / 1e9
     tf = flops / sec / 1e12
     bound = "hbm" if T * 2 < 2 * MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS else "mfma"   # flops per W byte = T
-    few = T <= 512
+    few = T <= 512 and T * wl.k * wl.r <= 8192
     return {
         "metric": "prefill latency, all adapted matrices, un-merged adapters with per-token decisions (us)",
         "value": t["mean"], "unit": "us", "n_gpus": 1, "steps": reps, "warmup": 2, "ms_per_step": t["mean"] * 1e-3,

@@ -290,16 +290,16 @@ adafuse_status adafuse_forward_dynamic(adafuse_ctx *ctx, const int32_t *idx, con
  * workspace  DEVICE, 16-byte aligned, at least adafuse_prefill_workspace_bytes() bytes
  *          (workspace_bytes is checked): the fp32 parts of the products whose inner dimension
  *          is split across workgroups (few tokens leave too few tiles to fill the chip) and,
- *          with more than 512 tokens, the scaled down-projections s g A x of every (token,
+ *          in the many-token form, the scaled down-projections s g A x of every (token,
  *          selection) as two bf16 planes (value and rounding remainder, 16 significant bits).
  *          Owned by the caller; its previous contents do not matter and nothing in it needs
  *          clearing.
  * Arithmetic: bf16 operands on the matrix cores, fp32 accumulation; the parts of a split inner
  * dimension are added in a fixed order: the same bits on every run.
- * Launches on `hip_stream`, no allocation, no synchronisation.  Up to 512 tokens: two (the
+ * Launches on `hip_stream`, no allocation, no synchronisation.  Few tokens (T <= 512 and T * k * r <= 8192): two (the
  * base product and the down-projection through the whole bank share one, cut into the same
- * number of parts; the second sums the parts and adds the up-projections in fp32).  More
- * tokens: three or four (down projection over the whole bank, gating, base product with the
+ * number of parts; the second sums the parts and adds the up-projections in fp32).
+ * Otherwise: three or four (down projection over the whole bank, gating, base product with the
  * up projection as further inner dimension, sum of the parts).  Needs an out-of-place context
  * (the base weights must be unmodified).
  * Errors: NULL pointer -> ERR_NULL; mat, T < 0, k out of range, in-place context, workspace
@@ -320,9 +320,9 @@ adafuse_status adafuse_prefill_workspace_bytes(const adafuse_ctx *ctx, int32_t m
  * of a layer; gate and up): the same results, y[i] = adafuse_prefill(mats[i]) up to the order
  * of the fp32 sums, with the launches shared.  The method's own argument for one batched
  * launch ("SGMM Kernel": many small launches leave the GPU under-used) holds here as well: at a
- * hundred tokens a launch costs more than streaming a 4096 x 4096 matrix once.  Up to 512
- * tokens the whole group takes two launches; with more tokens the matrices run one after the
- * other as in adafuse_prefill.
+ * hundred tokens a launch costs more than streaming a 4096 x 4096 matrix once.  In the
+ * few-token form the whole group takes two launches; otherwise the matrices run one after
+ * the other as in adafuse_prefill.
  * mats     HOST int32 [n], distinct matrix indices, 1 <= n <= 4, all with the same `in`
  *          (else ERR_SHAPE)
  * y        HOST array of n DEVICE pointers: y[i] fp32 [T][out of mats[i]], 16-byte aligned

@@ -663,7 +663,7 @@ PrefillCut prefill_cut(int T, int rows, int in)
     return c;
 }
 
-// Two forms.  FEW tokens (at most four token tiles: 512, measured level with the other form there): the bank products and the base products of ALL
+// Two forms.  FEW tokens (at most four token tiles and little adapter work, see below): the bank products and the base products of ALL
 // matrices of the group share ONE launch, cut into the same number of parts so that their workgroups
 // take equally long, and a second kernel sums the parts and adds the adapters in fp32 -- two launches
 // for the group, no bf16 pair, no dependent chain of four small kernels per matrix (at a hundred tokens a
@@ -671,6 +671,10 @@ PrefillCut prefill_cut(int T, int rows, int in)
 // as further inner dimension of the base product on the matrix cores (bank product, gate kernel, base
 // product, sum of the parts if there are any).
 constexpr int kPfFewTiles = 4;
+// ... and T k r at most this: the second kernel of the few-token form adds the adapters on the vector ALU
+// and re-reads the selected B rows for every token, which grows with T k r; measured on the 7B / 8B / 13B
+// shapes at ranks 8 to 128, the two forms cross between T k r = 6400 and 12800
+constexpr int64_t kPfFewWork = 8192;
 inline int prefill_units8(int units) { return ((units + 7) / 8) * 8; }
 
 struct PrefillPlan {
@@ -702,7 +706,7 @@ PrefillPlan prefill_plan(const adafuse_ctx *ctx, const int32_t *mats, int n, int
     const int bank_rows = ctx->E * ctx->r;
     const int in = ctx->mats[(size_t)mats[0]].in;
     pl.m_tiles = (T + kPfTileTokens - 1) / kPfTileTokens;
-    pl.few = pl.m_tiles <= kPfFewTiles;
+    pl.few = pl.m_tiles <= kPfFewTiles && (int64_t)T * k * ctx->r <= kPfFewWork;
     if (pl.few) {
         pl.bank_strips = (bank_rows + kPfTileRows - 1) / kPfTileRows;
         int total_strips = 0;
