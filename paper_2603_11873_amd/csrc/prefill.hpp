@@ -1,13 +1,19 @@
-// Prefill: many tokens through ONE adapted matrix, every token with its own routing
-// decision (section "Decoding Phase", prefill paragraph: one merged weight cannot serve
-// tokens that selected different experts, so the adapters stay un-merged here, Eq.2):
+// Prefill: many tokens through adapted matrices, every token with its own routing decision
+// (section "Decoding Phase", prefill paragraph: one merged weight cannot serve tokens that
+// selected different experts, so the adapters stay un-merged here, Eq.2):
 //   Y[t] = W_base x_t + s * sum_j g_{t,j} * B_{e_{t,j}} (A_{e_{t,j}} x_t),   t < T.
-// One matrix-core product kernel (v_mfma_f32_32x32x16_bf16, fp32 accumulation), used twice,
-// and two small element-wise kernels:
+// One matrix-core product kernel (v_mfma_f32_32x32x16_bf16, fp32 accumulation) and small
+// element-wise kernels around it, in two forms.
 //
-//   1. prefill_gemm_kernel on the A bank seen as one [E r][in] matrix: U = X A^T for ALL
-//      experts (dense: the bank is a fraction of W, and with more than a few dozen tokens
-//      every expert is selected by some token of a tile anyway).
+// FEW tokens (a launch costs more than streaming a matrix): two launches for a group of matrices
+// that share X.
+//   1. prefill_gemm_kernel on a batch of products: X W^T for every matrix of the group and
+//      U = X A^T for every bank seen as one [E r][in] matrix (ALL experts, dense: the bank is a
+//      fraction of W), all cut into the same number of parts of the inner dimension.
+//   2. prefill_finish_kernel: the parts summed in order, the adapters added in fp32 on the
+//      vector ALU (2 k r flops per output).
+// MANY tokens: matrix by matrix.
+//   1. prefill_gemm_kernel on the A bank: U = X A^T.
 //   2. prefill_gate_kernel: for every (token, selection) the expert's r columns of U times
 //      s * g, stored as a pair of bf16 planes hi + lo (16 significant bits), zero padded to
 //      a multiple of 8; a repeated selection of an expert is folded into the first.
@@ -20,17 +26,16 @@
 // The product kernel: a workgroup (4 waves side by side, 128 tokens x 64 rows each) owns 128 tokens
 // x 256 output rows and a range of the inner dimension; chunks of 64 inner indices of both
 // operands go straight into LDS (buffer_load ... lds, row-contiguous 128-byte lines: a wave
-// instruction moves 8 whole lines) in three stages -- two chunks, 64 KB of the matrix, in flight per
-// CU while a third is multiplied: at a hundred tokens the product is bound by streaming the matrix
-// once, and what is in flight decides the rate -- and each wave reads its operands from there in the matrix-core layout (the
-// 16-byte pieces of a line are permuted by the row number, so both the line-wise fill and the
-// column-of-pieces reads are conflict-free).  Loading operands straight from global memory in
-// the matrix-core layout (one row per lane) was the first version: 32 cache lines per wave
-// instruction, four times the address work in the texture path, and 10 x off the roofline.
-// With few tokens a launch has too few tiles to fill the chip, so the inner dimension is split
-// across workgroups and the parts are summed in a fixed order afterwards: no atomics, the
-// same bits on every run.  Lanes beyond T, the matrix edge or the split's range point outside
-// their buffer descriptor and read as zero.
+// instruction moves 8 whole lines) in three stages -- two chunks, 64 KB of the matrix, in flight
+// per CU while a third is multiplied -- and each wave reads its operands from there in the
+// matrix-core layout (the 16-byte pieces of a line are permuted by the row number, so both the
+// line-wise fill and the column-of-pieces reads are conflict-free).  Loading operands straight
+// from global memory in the matrix-core layout (one row per lane) was the first version: 32 cache
+// lines per wave instruction, four times the address work in the texture path, and 10 x off the
+// roofline.  With few tokens a launch has too few tiles to fill the chip, so the inner dimension
+// is split across workgroups and the parts are summed in a fixed order afterwards: no atomics,
+// the same bits on every run.  Lanes beyond T, the matrix edge or the split's range point
+// outside their buffer descriptor and read as zero.
 #pragma once
 #include "device_types.hpp"
 
